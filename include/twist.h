@@ -1,0 +1,192 @@
+/*
+ * twist.h - C ABI of the TwIST hot path on one AMD MI355X (gfx950).
+ *
+ * One training round of "Transformers with Independent Subnetwork Training" on one device:
+ *
+ *     twist_sample  ->  twist_extract (x S)  ->  { twist_subnet_fwd_bwd, twist_subnet_step }*  ->  twist_aggregate
+ *
+ * i.e. the subnet generator (Section 3.1, Algorithm 1), the dispatcher (Section 3.2), local training of
+ * each physically smaller dense subnet ("True TwIST", Section 4.1, with the activation-shift correction of
+ * Section 3.4) and the aggregator (Section 3.3).  The S subnets a cluster would spread over workers are
+ * run back-to-back on the one GPU.
+ *
+ * Conventions
+ *  - Every call returns a twist_status; nothing throws or aborts across this boundary.  On error the
+ *    out-parameters are left untouched and twist_last_error() describes the failure.
+ *  - "dev" pointers are HIP device pointers, "host" pointers ordinary host memory.  The library never
+ *    takes ownership of caller memory: full weights, subnet storage, workspace, inputs, targets and the
+ *    loss scalar stay owned by the caller (normally torch tensors) and must outlive the calls and the
+ *    handles that reference them.  The library owns only its handles (ctx, plan, subnet) and the small
+ *    index tables inside a plan, all released by the matching *_destroy call.
+ *  - All device work is enqueued on the HIP stream given to twist_create, asynchronously; calls do not
+ *    synchronise unless stated.
+ *  - Matrices are row-major [out_features, in_features]; element type is desc.dtype (fp32 or bf16).
+ *    A block ("unit") of kind TWIST_KIND_HEAD is one attention head: d_head rows of W^Q, W^K, W^V and of
+ *    their biases, and d_head columns of C^attn.  A block of kind TWIST_KIND_FFN is ffn_granule rows of
+ *    W^ffn (and of the gate matrix and the first bias) and ffn_granule columns of C^ffn.  Everything else
+ *    (output biases, norms, embeddings, final projection) is shared by all subnets (Section 3.1).
+ */
+#ifndef TWIST_H
+#define TWIST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TWIST_API __attribute__((visibility("default")))
+
+typedef enum {
+  TWIST_OK = 0,
+  TWIST_EINVAL = 1,      /* bad argument (null pointer, unknown enum, out-of-range index)           */
+  TWIST_ECONSTRAINT = 2, /* the size bound of Section 3.1 is violated                               */
+  TWIST_ESHAPE = 3,      /* a shape the kernels do not support, or a buffer that is too small        */
+  TWIST_ENOMEM = 4,      /* host or device allocation failed                                        */
+  TWIST_EHIP = 5         /* a HIP runtime call failed                                                */
+} twist_status;
+
+enum { TWIST_F32 = 0, TWIST_BF16 = 1 };                            /* desc.dtype        */
+enum { TWIST_ACT_GELU_TANH = 0, TWIST_ACT_RELU = 1, TWIST_ACT_SWIGLU = 2 }; /* desc.act  */
+enum { TWIST_NORM_LN = 0, TWIST_NORM_RMS = 1 };                    /* desc.norm         */
+enum { TWIST_KIND_HEAD = 0, TWIST_KIND_FFN = 1 };                  /* block kinds       */
+enum { TWIST_SCALE_NONE = 0, TWIST_SCALE_SQRT_RATIO = 1 };         /* sample.scale_mode */
+enum { TWIST_OPT_SGD = 0, TWIST_OPT_ADAMW = 1 };
+enum { TWIST_PARAM = 0, TWIST_GRAD = 1 };                          /* twist_subnet_view `what` */
+/* storage a subnet needs: weights only; + fp32 gradients (and fp32 master weights for bf16 models);
+ * + the two AdamW moment buffers. */
+enum { TWIST_STORE_PARAMS = 0, TWIST_STORE_GRADS = 1, TWIST_STORE_ADAMW = 2 };
+
+/* per-layer tensors, in the order of twist_full_weights.layer_tensors */
+enum {
+  TWIST_WQ = 0, TWIST_WK, TWIST_WV, TWIST_WO, TWIST_W_GATE, TWIST_W_UP, TWIST_W_DOWN,
+  TWIST_BQ, TWIST_BK, TWIST_BV, TWIST_BO, TWIST_B_UP, TWIST_B_DOWN,
+  TWIST_NORM1_W, TWIST_NORM1_B, TWIST_NORM2_W, TWIST_NORM2_B,
+  TWIST_N_LAYER_TENSORS
+};
+/* model-level tensors, all shared */
+enum {
+  TWIST_TOK_EMBED = 0, TWIST_POS_EMBED, TWIST_FINAL_NORM_W, TWIST_FINAL_NORM_B, TWIST_LM_HEAD,
+  TWIST_N_GLOBAL_TENSORS
+};
+
+/* The central model's shape (Section 2, "Problem formulation"; Appendix A.1-A.2 for the layer). */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_head, d_ff;
+  int32_t ffn_granule; /* neurons per FFN block, d_ff / R                                            */
+  int32_t vocab;       /* 0 = block-stack mode: activations in, mean-squared-error loss, no embedding */
+  int32_t max_seq;
+  int32_t act, norm;
+  int32_t has_bias;    /* linear layers carry biases (GPT-style)                                     */
+  int32_t tied_head;   /* final projection shares the token embedding                                */
+  int32_t use_rope;    /* rotary positions on Q,K (half-split pairing) instead of learned positions  */
+  int32_t dtype;
+  float norm_eps, rope_theta;
+} twist_model_desc;
+
+/* Device pointers of the central model.  layer_tensors is a HOST array of n_layers*TWIST_N_LAYER_TENSORS
+ * device pointers (layer-major); entries the architecture does not have are NULL. */
+typedef struct {
+  void *const *layer_tensors;
+  void *global_tensors[TWIST_N_GLOBAL_TENSORS];
+} twist_full_weights;
+
+/* Inputs of Algorithm 1, for every layer and both block kinds. */
+typedef struct {
+  int32_t S;                   /* number of subnets                                                  */
+  int32_t heads_sub;           /* N_sub for attention heads                                          */
+  int32_t ffn_units_sub;       /* N_sub for FFN blocks                                               */
+  const int32_t *common_heads; /* host, sorted unique, may be NULL when n_common_heads == 0          */
+  int32_t n_common_heads;
+  const int32_t *common_ffn;   /* host                                                               */
+  int32_t n_common_ffn;
+  const uint8_t *layer_shared; /* host [n_layers] or NULL; non-zero = layer kept whole in every subnet */
+  int32_t require_coverage;    /* 1 = training heuristic (every block assigned); 0 = deployment      */
+  int32_t scale_mode;
+  uint64_t seed, round;
+} twist_sample_desc;
+
+typedef struct {
+  int32_t kind;
+  float lr, beta1, beta2, eps, weight_decay; /* weight decay applies to matrices only */
+} twist_opt_desc;
+
+typedef struct twist_ctx twist_ctx;
+typedef struct twist_plan twist_plan;
+typedef struct twist_subnet twist_subnet;
+
+/* Create a context for one model shape.  hip_stream is a hipStream_t (NULL = the default stream).
+ * TWIST_ESHAPE if a dimension is not positive, d_ff is not a multiple of ffn_granule, or d_head is odd
+ * with rotary positions. */
+TWIST_API twist_status twist_create(const twist_model_desc *desc, void *hip_stream, twist_ctx **out);
+TWIST_API void twist_destroy(twist_ctx *ctx);
+/* Message of the last failing call on this ctx (or, with ctx == NULL, of the last failing call of the
+ * calling thread).  The string is owned by the library and valid until the next call. */
+TWIST_API const char *twist_last_error(const twist_ctx *ctx);
+
+/* Subnet generator, Algorithm 1 (Section 3.1): one blueprint A (S x N_sub, rows sorted) per layer and
+ * block kind, each from its own random stream keyed by (seed, round, layer, kind); plus, derived from A,
+ * inv[s][u] = position of block u in row s or -1, and count[u] = number of rows holding u (the denominator
+ * of the aggregation formula, Section 3.3).  Host integer work; the tables are also uploaded to the device
+ * (synchronous copy).  TWIST_ECONSTRAINT unless |C| <= N_sub <= N_full and, with require_coverage,
+ * N_full - |C| <= S (N_sub - |C|)  (the bound stated below Algorithm 1). */
+TWIST_API twist_status twist_sample(twist_ctx *ctx, const twist_sample_desc *desc, twist_plan **out);
+/* Borrowed views of one blueprint: idx [S][n_sub], inv [S][n_full], count [n_full], int32, host or device
+ * copies (on_device).  Any of the out pointers may be NULL.  Valid until twist_plan_destroy. */
+TWIST_API twist_status twist_plan_view(const twist_plan *plan, int32_t layer, int32_t kind, const int32_t **idx,
+                             const int32_t **inv, const int32_t **count, int32_t *n_sub, int32_t *n_full,
+                             int32_t on_device);
+TWIST_API void twist_plan_destroy(twist_plan *plan);
+
+/* Bytes of caller-provided device storage a subnet of this plan needs (same for every s). */
+TWIST_API twist_status twist_subnet_bytes(twist_ctx *ctx, const twist_plan *plan, int32_t store, size_t *bytes);
+
+/* Dispatcher (Section 3.2): materialise subnet s.  For every partitioned tensor the blocks named by row s
+ * of the blueprint are concatenated, in row order, into a smaller dense matrix; shared tensors are copied.
+ * `storage` (dev, 256-byte aligned, storage_bytes >= twist_subnet_bytes) receives the subnet and stays
+ * owned by the caller; gradient and optimizer regions, if requested, are zeroed and fp32 master weights are
+ * initialised from the extracted values.  Inside the subnet W^Q,W^K,W^V are stored as one [3 H' d_head, d]
+ * matrix and gate/up as one [2 F', d] matrix; twist_subnet_view hides that. */
+TWIST_API twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int32_t s,
+                           void *storage, size_t storage_bytes, int32_t store, twist_subnet **out);
+/* Device pointer and [rows, cols] shape (cols = 1 for vectors) of one subnet tensor; layer = -1 selects the
+ * model-level tensors.  what = TWIST_PARAM gives desc.dtype data, TWIST_GRAD the fp32 gradient. */
+TWIST_API twist_status twist_subnet_view(const twist_subnet *sub, int32_t layer, int32_t tensor, int32_t what,
+                               void **dev, int64_t shape[2]);
+TWIST_API void twist_subnet_destroy(twist_subnet *sub);
+
+/* Bytes of device workspace twist_subnet_fwd_bwd needs for a batch of B sequences of N tokens. */
+TWIST_API twist_status twist_workspace_bytes(twist_ctx *ctx, const twist_subnet *sub, int32_t B, int32_t N, size_t *bytes);
+
+/* One forward + backward pass of the dense subnet (Section 4.1 "True TwIST"; layer of Appendix A.2, causal
+ * attention).  Each module's output is multiplied by sqrt(N_full / N_sub) before its residual add when the
+ * plan was sampled with TWIST_SCALE_SQRT_RATIO (Section 3.4).
+ *   vocab > 0 : inputs  = int32 token ids [B, N] (dev), targets = int32 ids [B, N] (dev, already shifted);
+ *               loss = mean cross-entropy over the B*N positions.
+ *   vocab = 0 : inputs  = activations [B, N, d_model] in desc.dtype, targets likewise; loss = mean squared
+ *               error over all B*N*d_model elements of the last layer's output.
+ * Writes the fp32 loss to loss_dev and OVERWRITES the subnet's gradient buffers with dLoss/dparam.
+ * bf16 models: bf16 operands, fp32 accumulation, fp32 residual stream, softmax and norm statistics.
+ * TWIST_ESHAPE if the subnet has no gradient storage, N > max_seq, the workspace is too small, or a
+ * dimension is outside what the kernels cover (d_head in {32, 64, 128}; d_model, widths multiples of 8). */
+TWIST_API twist_status twist_subnet_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets,
+                                  int32_t B, int32_t N, void *workspace, size_t workspace_bytes, float *loss_dev);
+
+/* Local optimizer step on every subnet parameter from the current gradients: SGD  w -= lr g,  or AdamW
+ * (bias-corrected, decoupled decay on matrices only; needs TWIST_STORE_ADAMW).  bf16 models update fp32
+ * master weights and re-round the bf16 copy. */
+TWIST_API twist_status twist_subnet_step(twist_ctx *ctx, twist_subnet *sub, const twist_opt_desc *opt);
+
+/* Aggregator (Section 3.3): for every central parameter p,  p <- sum_i p_i [p in W_i] / sum_i [p in W_i]
+ * over the given subnets (a parameter held by none of them keeps its value); shared tensors become the
+ * mean over the given subnets.  subs[i] must have been extracted from this plan; any subset of the S
+ * subnets may be passed (n_subs >= 1).  Sums are formed in fp32 in the order given, divided, and rounded
+ * once to desc.dtype; a parameter with a single owner is copied bit-exactly.  Updates `inout` in place. */
+TWIST_API twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, twist_subnet *const *subs, int32_t n_subs,
+                             const twist_full_weights *inout);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWIST_H */

@@ -1,0 +1,243 @@
+"""ctypes binding with the same names as include/twist.h, plus small holder classes that keep the
+torch tensors behind the raw pointers alive.  PyTorch is used for device memory and streams only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+__all__ = [
+    "TwistError", "ModelDesc", "SampleDesc", "OptDesc", "lib", "Context", "Plan", "Subnet", "FullWeights",
+    "LAYER_TENSORS", "GLOBAL_TENSORS", "F32", "BF16", "KIND_HEAD", "KIND_FFN", "STORE_PARAMS", "STORE_GRADS",
+    "STORE_ADAMW", "OPT_SGD", "OPT_ADAMW", "SCALE_NONE", "SCALE_SQRT_RATIO", "desc_from_cfg",
+]
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtwist.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or paper_2511_03983_amd/build.py) first; there is no fallback path")
+lib = C.CDLL(_LIB_PATH)
+
+F32, BF16 = 0, 1
+ACT = {"gelu_tanh": 0, "relu": 1, "swiglu": 2}
+NORM = {"ln": 0, "rms": 1}
+KIND_HEAD, KIND_FFN = 0, 1
+SCALE_NONE, SCALE_SQRT_RATIO = 0, 1
+OPT_SGD, OPT_ADAMW = 0, 1
+PARAM, GRAD = 0, 1
+STORE_PARAMS, STORE_GRADS, STORE_ADAMW = 0, 1, 2
+LAYER_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "bq", "bk", "bv", "bo", "b_up", "b_down",
+                 "norm1_w", "norm1_b", "norm2_w", "norm2_b")
+GLOBAL_TENSORS = ("tok_embed", "pos_embed", "final_norm_w", "final_norm_b", "lm_head")
+_STATUS = {1: "EINVAL", 2: "ECONSTRAINT", 3: "ESHAPE", 4: "ENOMEM", 5: "EHIP"}
+
+
+class TwistError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"TWIST_{_STATUS.get(status, status)}: {msg}")
+        self.status = status
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "d_head", "d_ff", "ffn_granule", "vocab",
+                                         "max_seq", "act", "norm", "has_bias", "tied_head", "use_rope", "dtype")] + \
+               [("norm_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class FullWeightsC(C.Structure):
+    _fields_ = [("layer_tensors", C.POINTER(C.c_void_p)), ("global_tensors", C.c_void_p * len(GLOBAL_TENSORS))]
+
+
+class SampleDesc(C.Structure):
+    _fields_ = [("S", C.c_int32), ("heads_sub", C.c_int32), ("ffn_units_sub", C.c_int32),
+                ("common_heads", C.POINTER(C.c_int32)), ("n_common_heads", C.c_int32),
+                ("common_ffn", C.POINTER(C.c_int32)), ("n_common_ffn", C.c_int32),
+                ("layer_shared", C.POINTER(C.c_uint8)), ("require_coverage", C.c_int32), ("scale_mode", C.c_int32),
+                ("seed", C.c_uint64), ("round", C.c_uint64)]
+
+
+class OptDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
+
+
+_vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
+_PI32 = C.POINTER(C.c_int32)
+_SIGS = {
+    "twist_create": ([C.POINTER(ModelDesc), _vp, C.POINTER(_vp)], _i32),
+    "twist_destroy": ([_vp], None),
+    "twist_last_error": ([_vp], C.c_char_p),
+    "twist_sample": ([_vp, C.POINTER(SampleDesc), C.POINTER(_vp)], _i32),
+    "twist_plan_view": ([_vp, _i32, _i32, C.POINTER(_PI32), C.POINTER(_PI32), C.POINTER(_PI32), _PI32, _PI32, _i32], _i32),
+    "twist_plan_destroy": ([_vp], None),
+    "twist_subnet_bytes": ([_vp, _vp, _i32, C.POINTER(_sz)], _i32),
+    "twist_extract": ([_vp, _vp, C.POINTER(FullWeightsC), _i32, _vp, _sz, _i32, C.POINTER(_vp)], _i32),
+    "twist_subnet_view": ([_vp, _i32, _i32, _i32, C.POINTER(_vp), C.POINTER(C.c_int64)], _i32),
+    "twist_subnet_destroy": ([_vp], None),
+    "twist_workspace_bytes": ([_vp, _vp, _i32, _i32, C.POINTER(_sz)], _i32),
+    "twist_subnet_fwd_bwd": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
+    "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
+    "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
+}
+for _name, (_args, _res) in _SIGS.items():
+    _f = getattr(lib, _name)          # AttributeError here = the library lacks a declared entry point
+    _f.argtypes, _f.restype = _args, _res
+EXPORTS = tuple(_SIGS)
+
+
+def _check(status, ctx=None):
+    if status != 0:
+        raise TwistError(status, (lib.twist_last_error(ctx) or b"").decode())
+
+
+def desc_from_cfg(cfg) -> ModelDesc:
+    """Build a ModelDesc from any object with the model-shape attributes (see include/twist.h)."""
+    return ModelDesc(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.d_head, cfg.d_ff, cfg.ffn_granule, cfg.vocab, cfg.max_seq,
+                     ACT[cfg.act], NORM[cfg.norm], int(cfg.has_bias), int(cfg.tied_head), int(cfg.rope),
+                     BF16 if cfg.dtype == "bf16" else F32, cfg.norm_eps, cfg.rope_theta)
+
+
+class Context:
+    """twist_create / twist_destroy.  Work is enqueued on `stream` (default: torch's current stream)."""
+
+    def __init__(self, desc: ModelDesc, stream: torch.cuda.Stream | None = None):
+        self.desc = desc
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = _vp()
+        _check(lib.twist_create(C.byref(desc), _vp(self.stream.cuda_stream), C.byref(h)))
+        self.h = h
+        self.torch_dtype = torch.bfloat16 if desc.dtype == BF16 else torch.float32
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.twist_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    # ---- the C entry points, by name -----------------------------------------------------------
+    def twist_sample(self, S, heads_sub, ffn_units_sub, seed=0, rnd=0, common_heads=(), common_ffn=(), layer_shared=None,
+                     require_coverage=True, scale_mode=SCALE_SQRT_RATIO) -> "Plan":
+        ch = (C.c_int32 * len(common_heads))(*common_heads)
+        cf = (C.c_int32 * len(common_ffn))(*common_ffn)
+        ls = (C.c_uint8 * self.desc.n_layers)(*[int(bool(x)) for x in layer_shared]) if layer_shared is not None else None
+        sd = SampleDesc(S, heads_sub, ffn_units_sub, ch, len(common_heads), cf, len(common_ffn), ls,
+                        int(require_coverage), scale_mode, seed, rnd)
+        h = _vp()
+        _check(lib.twist_sample(self.h, C.byref(sd), C.byref(h)), self.h)
+        return Plan(self, h, S)
+
+    def twist_subnet_bytes(self, plan: "Plan", store=STORE_PARAMS) -> int:
+        n = _sz()
+        _check(lib.twist_subnet_bytes(self.h, plan.h, store, C.byref(n)), self.h)
+        return n.value
+
+    def twist_extract(self, plan: "Plan", full: "FullWeights", s: int, store=STORE_PARAMS, storage: torch.Tensor | None = None) -> "Subnet":
+        if storage is None:
+            storage = torch.empty(self.twist_subnet_bytes(plan, store), dtype=torch.uint8, device="cuda")
+        h = _vp()
+        _check(lib.twist_extract(self.h, plan.h, C.byref(full.c), s, _vp(storage.data_ptr()), storage.numel(), store, C.byref(h)), self.h)
+        return Subnet(self, plan, h, storage, s)
+
+    def twist_workspace_bytes(self, sub: "Subnet", B: int, N: int) -> int:
+        n = _sz()
+        _check(lib.twist_workspace_bytes(self.h, sub.h, B, N, C.byref(n)), self.h)
+        return n.value
+
+    def twist_subnet_fwd_bwd(self, sub: "Subnet", inputs: torch.Tensor, targets: torch.Tensor, workspace: torch.Tensor,
+                             loss: torch.Tensor) -> None:
+        B, N = inputs.shape[0], inputs.shape[1]
+        _check(lib.twist_subnet_fwd_bwd(self.h, sub.h, _vp(inputs.data_ptr()), _vp(targets.data_ptr()), B, N,
+                                        _vp(workspace.data_ptr()), workspace.numel(), _vp(loss.data_ptr())), self.h)
+
+    def twist_subnet_step(self, sub: "Subnet", kind=OPT_SGD, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0) -> None:
+        od = OptDesc(kind, lr, beta1, beta2, eps, weight_decay)
+        _check(lib.twist_subnet_step(self.h, sub.h, C.byref(od)), self.h)
+
+    def twist_aggregate(self, plan: "Plan", subs, full: "FullWeights") -> None:
+        arr = (_vp * len(subs))(*[s.h for s in subs])
+        _check(lib.twist_aggregate(self.h, plan.h, arr, len(subs), C.byref(full.c)), self.h)
+
+
+class Plan:
+    def __init__(self, ctx: Context, h, S):
+        self.ctx, self.h, self.S = ctx, h, S
+
+    def twist_plan_view(self, layer: int, kind: int):
+        """Host copies of (idx [S, n_sub], inv [S, n_full], count [n_full]) as int32 torch tensors."""
+        idx, inv, cnt = _PI32(), _PI32(), _PI32()
+        ns, nf = C.c_int32(), C.c_int32()
+        _check(lib.twist_plan_view(self.h, layer, kind, C.byref(idx), C.byref(inv), C.byref(cnt), C.byref(ns), C.byref(nf), 0), self.ctx.h)
+        S, ns, nf = self.S, ns.value, nf.value
+        as_t = lambda p, n: torch.tensor(p[:n], dtype=torch.int32)
+        return as_t(idx, S * ns).view(S, ns), as_t(inv, S * nf).view(S, nf), as_t(cnt, nf)
+
+    def device_tables(self, layer: int, kind: int):
+        """Raw device addresses of (idx, inv, count) and (n_sub, n_full)."""
+        idx, inv, cnt = _PI32(), _PI32(), _PI32()
+        ns, nf = C.c_int32(), C.c_int32()
+        _check(lib.twist_plan_view(self.h, layer, kind, C.byref(idx), C.byref(inv), C.byref(cnt), C.byref(ns), C.byref(nf), 1), self.ctx.h)
+        addr = lambda p: C.cast(p, C.c_void_p).value
+        return addr(idx), addr(inv), addr(cnt), ns.value, nf.value
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.twist_plan_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class Subnet:
+    def __init__(self, ctx: Context, plan: Plan, h, storage: torch.Tensor, s: int):
+        self.ctx, self.plan, self.h, self.storage, self.s = ctx, plan, h, storage, s
+
+    def twist_subnet_view(self, layer: int, tensor: str | int, what=PARAM) -> torch.Tensor:
+        """A torch view (no copy) of one subnet tensor inside the caller-owned storage."""
+        names = GLOBAL_TENSORS if layer < 0 else LAYER_TENSORS
+        t = names.index(tensor) if isinstance(tensor, str) else tensor
+        dev, shape = _vp(), (C.c_int64 * 2)()
+        _check(lib.twist_subnet_view(self.h, layer, t, what, C.byref(dev), shape), self.ctx.h)
+        dt = self.ctx.torch_dtype if what == PARAM else torch.float32
+        n = shape[0] * shape[1]
+        off = dev.value - self.storage.data_ptr()
+        v = self.storage[off: off + n * dt.itemsize].view(dt)
+        return v.view(shape[0], shape[1]) if shape[1] > 1 else v
+
+    def has(self, layer: int, tensor: str) -> bool:
+        try:
+            self.twist_subnet_view(layer, tensor)
+            return True
+        except TwistError:
+            return False
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.twist_subnet_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class FullWeights:
+    """Pointer table over caller-owned torch tensors: layers = [ {name: tensor} ], globals_ = {name: tensor}."""
+
+    def __init__(self, layers, globals_=None):
+        self.layers, self.globals = layers, dict(globals_ or {})
+        n = len(layers) * len(LAYER_TENSORS)
+        self._arr = (C.c_void_p * n)()
+        for l, lw in enumerate(layers):
+            for t, name in enumerate(LAYER_TENSORS):
+                w = lw.get(name)
+                if w is not None:
+                    assert w.is_cuda and w.is_contiguous()
+                    self._arr[l * len(LAYER_TENSORS) + t] = w.data_ptr()
+        g = (C.c_void_p * len(GLOBAL_TENSORS))()
+        for t, name in enumerate(GLOBAL_TENSORS):
+            w = self.globals.get(name)
+            if w is not None:
+                assert w.is_cuda and w.is_contiguous()
+                g[t] = w.data_ptr()
+        self.c = FullWeightsC(C.cast(self._arr, C.POINTER(C.c_void_p)), g)

@@ -1,0 +1,367 @@
+// Dispatcher and aggregator data movement (Sections 3.2 and 3.3): segment gather and pull scatter-average.
+//
+// Every partitioned tensor is seen as `rows` rows of segments of Q elements.  extract copies, for each row,
+// the n_sub segments a blueprint row names into a dense row; aggregate walks the CENTRAL tensor and, for
+// each of its segments, pulls the matching segment from every subnet that holds it (through the inverse
+// table), sums in fp32 in subnet order, divides by the number of owners and stores once.  No atomics, no
+// staging buffer: every byte is read once and written once, so results are run-to-run bit-identical.
+//
+// All tensors of one layer go into one launch: a workgroup finds its job by its block index.  Two data
+// paths: 16-byte vectors when segments are 16-byte multiples (whole matrix rows, head columns), and an
+// element path with lane-consecutive elements (neuron columns of the down projection), where a wave's 64
+// lanes read a short contiguous span of the source row and write one full 128-byte line.
+#include "twist_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int ES> struct VecOf;
+template <> struct VecOf<2> { using vec = u32x4; using elem = uint16_t; static constexpr int N = 8; };
+template <> struct VecOf<4> { using vec = u32x4; using elem = uint32_t; static constexpr int N = 4; };
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                  // round to nearest even
+  return u >> 16;
+}
+
+__device__ __forceinline__ int find_job(const MoveLaunch &ml, int blk) {
+  int j = 0;
+#pragma unroll 1
+  for (int i = 1; i < ml.n_jobs; ++i)
+    if (blk >= ml.job[i].blk_begin) j = i;
+  return j;
+}
+
+// ------------------------------------------------------------------------------------------- extract
+template <int ES, int TR, int TU>
+__device__ __forceinline__ void gather_vec(const MoveJob &jb, char *dst_base, int lb) {
+  using V = typename VecOf<ES>::vec;
+  constexpr int VN = VecOf<ES>::N;
+  const int qv = jb.Q / VN;
+  const int64_t Ws = (int64_t)jb.n_sub * qv, Wf = (int64_t)jb.n_full * qv;
+  const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
+  const V *src = reinterpret_cast<const V *>(jb.full);
+  V *dst = reinterpret_cast<V *>(dst_base + jb.sub_off * ES);
+  V val[TR][TU];
+  int64_t dv[TU], sv[TU];
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
+    dv[u] = v < Ws ? v : -1;
+    if (v < Ws) {
+      int k = (int)(v / qv);
+      int j = (int)(v - (int64_t)k * qv);
+      sv[u] = jb.table ? (int64_t)jb.table[k] * qv + j : v;
+    } else {
+      sv[u] = 0;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < TR; ++r) {
+    int row = rt * TR + r;
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
+      if (row < jb.rows && dv[u] >= 0) val[r][u] = __builtin_nontemporal_load(&src[row * Wf + sv[u]]);
+  }
+#pragma unroll
+  for (int r = 0; r < TR; ++r) {
+    int row = rt * TR + r;
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
+      if (row < jb.rows && dv[u] >= 0) __builtin_nontemporal_store(val[r][u], &dst[row * Ws + dv[u]]);
+  }
+}
+
+template <int ES>
+__device__ __forceinline__ void gather_elem(const MoveJob &jb, char *dst_base, int lb) {
+  using E = typename VecOf<ES>::elem;
+  constexpr int TU = 2;
+  const int64_t Ws = (int64_t)jb.n_sub * jb.Q, Wf = (int64_t)jb.n_full * jb.Q;
+  const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
+  const E *src = reinterpret_cast<const E *>(jb.full);
+  E *dst = reinterpret_cast<E *>(dst_base + jb.sub_off * ES);
+  int64_t dv[TU], sv[TU];
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
+    dv[u] = v < Ws ? v : -1;
+    sv[u] = 0;
+    if (v < Ws) {
+      int k = (int)(v / jb.Q);
+      int j = (int)(v - (int64_t)k * jb.Q);
+      sv[u] = jb.table ? (int64_t)jb.table[k] * jb.Q + j : v;
+    }
+  }
+  const int r0 = rt * jb.tile_rows;
+  const int r1 = min(r0 + jb.tile_rows, jb.rows);
+  int row = r0;
+  for (; row + 4 <= r1; row += 4) {
+    E val[4][TU];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int u = 0; u < TU; ++u)
+        if (dv[u] >= 0) val[r][u] = src[(row + r) * Wf + sv[u]];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int u = 0; u < TU; ++u)
+        if (dv[u] >= 0) dst[(row + r) * Ws + dv[u]] = val[r][u];
+  }
+  for (; row < r1; ++row)
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
+      if (dv[u] >= 0) dst[row * Ws + dv[u]] = src[row * Wf + sv[u]];
+}
+
+template <int ES>
+__global__ __launch_bounds__(kThreads) void extract_kernel(const MoveLaunch ml) {
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  const int lb = blockIdx.x - jb.blk_begin;
+  char *dst_base = const_cast<char *>(ml.sub_base[0]);
+  if (jb.vec) {
+    if (jb.tile_u == 4) gather_vec<ES, 1, 4>(jb, dst_base, lb);
+    else if (jb.tile_u == 2) gather_vec<ES, 2, 2>(jb, dst_base, lb);
+    else gather_vec<ES, 4, 1>(jb, dst_base, lb);
+  } else {
+    gather_elem<ES>(jb, dst_base, lb);
+  }
+}
+
+// ------------------------------------------------------------------------------------------- aggregate
+template <int ES> struct Acc;
+template <> struct Acc<2> {
+  float a[8];
+  __device__ __forceinline__ void set(const u32x4 &v) {
+    a[0] = bf16_to_f32(v.x & 0xffff); a[1] = bf16_to_f32(v.x >> 16);
+    a[2] = bf16_to_f32(v.y & 0xffff); a[3] = bf16_to_f32(v.y >> 16);
+    a[4] = bf16_to_f32(v.z & 0xffff); a[5] = bf16_to_f32(v.z >> 16);
+    a[6] = bf16_to_f32(v.w & 0xffff); a[7] = bf16_to_f32(v.w >> 16);
+  }
+  __device__ __forceinline__ void add(const u32x4 &v) {
+    a[0] += bf16_to_f32(v.x & 0xffff); a[1] += bf16_to_f32(v.x >> 16);
+    a[2] += bf16_to_f32(v.y & 0xffff); a[3] += bf16_to_f32(v.y >> 16);
+    a[4] += bf16_to_f32(v.z & 0xffff); a[5] += bf16_to_f32(v.z >> 16);
+    a[6] += bf16_to_f32(v.w & 0xffff); a[7] += bf16_to_f32(v.w >> 16);
+  }
+  __device__ __forceinline__ u32x4 mean(int cnt) const {
+    const float c = (float)cnt;
+    u32x4 o;
+    o.x = f32_to_bf16(a[0] / c) | (f32_to_bf16(a[1] / c) << 16);
+    o.y = f32_to_bf16(a[2] / c) | (f32_to_bf16(a[3] / c) << 16);
+    o.z = f32_to_bf16(a[4] / c) | (f32_to_bf16(a[5] / c) << 16);
+    o.w = f32_to_bf16(a[6] / c) | (f32_to_bf16(a[7] / c) << 16);
+    return o;
+  }
+};
+template <> struct Acc<4> {
+  float a[4];
+  __device__ __forceinline__ void set(const u32x4 &v) {
+    a[0] = __uint_as_float(v.x); a[1] = __uint_as_float(v.y); a[2] = __uint_as_float(v.z); a[3] = __uint_as_float(v.w);
+  }
+  __device__ __forceinline__ void add(const u32x4 &v) {
+    a[0] += __uint_as_float(v.x); a[1] += __uint_as_float(v.y); a[2] += __uint_as_float(v.z); a[3] += __uint_as_float(v.w);
+  }
+  __device__ __forceinline__ u32x4 mean(int cnt) const {
+    const float c = (float)cnt;
+    u32x4 o;
+    o.x = __float_as_uint(a[0] / c); o.y = __float_as_uint(a[1] / c);
+    o.z = __float_as_uint(a[2] / c); o.w = __float_as_uint(a[3] / c);
+    return o;
+  }
+};
+
+template <int ES> __device__ __forceinline__ float elem_to_f32(typename VecOf<ES>::elem e);
+template <> __device__ __forceinline__ float elem_to_f32<2>(uint16_t e) { return bf16_to_f32(e); }
+template <> __device__ __forceinline__ float elem_to_f32<4>(uint32_t e) { return __uint_as_float(e); }
+template <int ES> __device__ __forceinline__ typename VecOf<ES>::elem f32_to_elem(float f);
+template <> __device__ __forceinline__ uint16_t f32_to_elem<2>(float f) { return (uint16_t)f32_to_bf16(f); }
+template <> __device__ __forceinline__ uint32_t f32_to_elem<4>(float f) { return __float_as_uint(f); }
+
+constexpr int kChunk = 8;  // subnets whose loads are issued together
+
+template <int ES, int TR, int TU>
+__device__ __forceinline__ void pull_vec(const MoveLaunch &ml, const MoveJob &jb, int lb) {
+  using V = typename VecOf<ES>::vec;
+  constexpr int VN = VecOf<ES>::N;
+  const int qv = jb.Q / VN;
+  const int64_t Ws = (int64_t)jb.n_sub * qv, Wf = (int64_t)jb.n_full * qv;
+  const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
+  V *full = reinterpret_cast<V *>(const_cast<void *>(jb.full));
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
+    if (v >= Wf) continue;
+    const int unit = (int)(v / qv);
+    const int j = (int)(v - (int64_t)unit * qv);
+    Acc<ES> acc[TR];
+    int cnt = 0;
+    for (int c0 = 0; c0 < ml.n_subs; c0 += kChunk) {
+      int p[kChunk];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        p[i] = -1;
+        if (c0 + i < ml.n_subs) p[i] = jb.table ? jb.table[(int64_t)ml.sub_row[c0 + i] * jb.n_full + unit] : 0;
+      }
+      V val[kChunk][TR];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+        if (p[i] >= 0) {
+          const V *sp = reinterpret_cast<const V *>(ml.sub_base[c0 + i] + jb.sub_off * ES) + (int64_t)p[i] * qv + j;
+#pragma unroll
+          for (int r = 0; r < TR; ++r) {
+            const int row = rt * TR + r;
+            if (row < jb.rows) val[i][r] = __builtin_nontemporal_load(&sp[row * Ws]);
+          }
+        }
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+        if (p[i] >= 0) {
+#pragma unroll
+          for (int r = 0; r < TR; ++r) {
+            if (cnt == 0) acc[r].set(val[i][r]); else acc[r].add(val[i][r]);
+          }
+          ++cnt;
+        }
+    }
+    if (cnt > 0) {
+#pragma unroll
+      for (int r = 0; r < TR; ++r) {
+        const int row = rt * TR + r;
+        if (row < jb.rows) __builtin_nontemporal_store(acc[r].mean(cnt), &full[row * Wf + v]);
+      }
+    }
+  }
+}
+
+template <int ES>
+__device__ __forceinline__ void pull_elem(const MoveLaunch &ml, const MoveJob &jb, int lb) {
+  using E = typename VecOf<ES>::elem;
+  constexpr int TU = 2;
+  const int64_t Ws = (int64_t)jb.n_sub * jb.Q, Wf = (int64_t)jb.n_full * jb.Q;
+  const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
+  E *full = reinterpret_cast<E *>(const_cast<void *>(jb.full));
+  const int r0 = rt * jb.tile_rows;
+  const int r1 = min(r0 + jb.tile_rows, jb.rows);
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
+    if (v >= Wf) continue;
+    const int unit = (int)(v / jb.Q);
+    const int j = (int)(v - (int64_t)unit * jb.Q);
+    if (ml.n_subs <= kChunk) {
+      // common case: the positions of this element in all subnets fit in registers and are reused
+      // for every row of the tile
+      int64_t pos[kChunk];
+      int have = 0;
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        pos[i] = -1;
+        if (i < ml.n_subs) {
+          int p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+          if (p >= 0) { pos[i] = (int64_t)p * jb.Q + j; ++have; }
+        }
+      }
+      if (have == 0) continue;  // no owner: the central value stays
+      const float c = (float)have;
+      for (int row = r0; row < r1; ++row) {
+        E val[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          if (pos[i] >= 0) val[i] = reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES)[row * Ws + pos[i]];
+        float acc = 0.f;
+        bool first = true;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+          if (pos[i] >= 0) { acc = first ? elem_to_f32<ES>(val[i]) : acc + elem_to_f32<ES>(val[i]); first = false; }
+        full[row * Wf + v] = f32_to_elem<ES>(acc / c);
+      }
+    } else {
+      // more subnets than one chunk: plain loop over all of them per row
+      for (int row = r0; row < r1; ++row) {
+        float acc = 0.f;
+        int cnt = 0;
+        for (int i = 0; i < ml.n_subs; ++i) {
+          int p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+          if (p >= 0) {
+            float x = elem_to_f32<ES>(reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES)[row * Ws + (int64_t)p * jb.Q + j]);
+            acc = cnt ? acc + x : x;
+            ++cnt;
+          }
+        }
+        if (cnt) full[row * Wf + v] = f32_to_elem<ES>(acc / (float)cnt);
+      }
+    }
+  }
+}
+
+template <int ES>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const MoveLaunch ml) {
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  const int lb = blockIdx.x - jb.blk_begin;
+  if (jb.vec) {
+    if (jb.tile_u == 4) pull_vec<ES, 1, 4>(ml, jb, lb);
+    else if (jb.tile_u == 2) pull_vec<ES, 2, 2>(ml, jb, lb);
+    else pull_vec<ES, 4, 1>(ml, jb, lb);
+  } else {
+    pull_elem<ES>(ml, jb, lb);
+  }
+}
+
+// ------------------------------------------------------------------------------------------- helpers
+template <int ES>
+__global__ __launch_bounds__(kThreads) void to_f32_kernel(const void *src, float *dst, int64_t n) {
+  using E = typename VecOf<ES>::elem;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
+    dst[i] = elem_to_f32<ES>(reinterpret_cast<const E *>(src)[i]);
+}
+
+__global__ __launch_bounds__(kThreads) void zero_kernel(u32x4 *dst, int64_t n_vec) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += stride) dst[i] = u32x4{0, 0, 0, 0};
+}
+
+}  // namespace
+
+twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks) {
+  if (total_blocks <= 0) return TWIST_OK;
+  if (ctx->esize() == 2) hipLaunchKernelGGL(extract_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  else hipLaunchKernelGGL(extract_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks) {
+  if (total_blocks <= 0) return TWIST_OK;
+  if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  else hipLaunchKernelGGL(aggregate_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_launch_to_f32(twist_ctx *ctx, const void *src, float *dst, int64_t n) {
+  if (n <= 0) return TWIST_OK;
+  int blocks = (int)std::min<int64_t>((n + kThreads - 1) / kThreads, 256 * 16);
+  if (ctx->esize() == 2) hipLaunchKernelGGL(to_f32_kernel<2>, dim3(blocks), dim3(kThreads), 0, ctx->stream, src, dst, n);
+  else hipLaunchKernelGGL(to_f32_kernel<4>, dim3(blocks), dim3(kThreads), 0, ctx->stream, src, dst, n);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_launch_zero(twist_ctx *ctx, void *dst, size_t bytes) {
+  if (bytes == 0) return TWIST_OK;
+  int64_t nv = (int64_t)(bytes / 16);  // callers pass multiples of 16
+  int blocks = (int)std::min<int64_t>((nv + kThreads - 1) / kThreads, 256 * 16);
+  hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(kThreads), 0, ctx->stream, reinterpret_cast<u32x4 *>(dst), nv);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}

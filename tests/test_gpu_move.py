@@ -1,0 +1,271 @@
+"""GPU parity of twist_sample / twist_extract / twist_aggregate against the CPU checker, through the C ABI."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from helpers import bf16_ulp_distance, model_to_numpy, rel_fro, subnet_to_numpy, to_device, to_numpy
+from oracle import move as omove
+from oracle.sample import sample_plan
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(lib, cfg):
+    return lib.Context(lib.desc_from_cfg(cfg))
+
+
+# ------------------------------------------------------------------------------------------ sample
+SAMPLE_CASES = [
+    # (n_layers, heads, d_head, d_ff, granule, S, heads_sub, ffn_sub, common_heads, common_ffn, shared, coverage)
+    (2, 4, 32, 512, 1, 2, 2, 256, (), (), None, True),                    # workload 1: tight bound, partition
+    (3, 12, 64, 3072, 1, 4, 3, 768, (), (), None, True),                  # workload 2
+    (2, 16, 128, 5632, 1, 4, 8, 2816, (), (), None, True),                # workload 3: overlap, covered
+    (2, 32, 128, 11008, 1, 8, 16, 5504, (), (), None, True),              # workload 4
+    (4, 12, 64, 3072, 256, 4, 6, 8, (0, 5), (3,), [1, 0, 0, 1], True),    # blocks of 256 neurons, common sets, shared layers
+    (2, 32, 128, 11008, 1, 1, 16, 5504, (), (), None, False),             # deployment: one subnet, no coverage
+    (2, 7, 32, 33, 3, 3, 5, 6, (2,), (), None, True),                     # odd sizes
+]
+
+
+@pytest.mark.parametrize("case", SAMPLE_CASES)
+def test_sample_matches_oracle_bit_exactly(lib, case):
+    L, H, dh, F, g, S, hs, fs, ch, cf, shared, cov = case
+    cfg = si.ModelCfg(n_layers=L, d_model=64, n_heads=H, d_head=dh, d_ff=F, ffn_granule=g)
+    ctx = _ctx(lib, cfg)
+    for seed, rnd in ((0, 0), (12345, 7)):
+        plan = ctx.twist_sample(S, hs, fs, seed=seed, rnd=rnd, common_heads=ch, common_ffn=cf, layer_shared=shared, require_coverage=cov)
+        want = sample_plan(L, H, F // g, S, hs, fs, seed, rnd, ch, cf, shared, cov)
+        for l in range(L):
+            for kind in (0, 1):
+                idx, inv, cnt = plan.twist_plan_view(l, kind)
+                w = want[l][kind]
+                assert idx.tolist() == w["idx"], (l, kind)
+                assert inv.tolist() == w["inv"]
+                assert cnt.tolist() == w["count"]
+                # the device copies hold the same integers
+                d_idx, d_inv, d_cnt, ns, nf = plan.device_tables(l, kind)
+                assert (ns, nf) == (w["n_sub"], w["n_full"])
+        plan.close()
+
+
+def test_sample_rejects_bound_violations(lib):
+    ctx = _ctx(lib, si.CFG1)
+    with pytest.raises(lib.TwistError) as e:
+        ctx.twist_sample(2, 1, 256)
+    assert e.value.status == 2
+    with pytest.raises(lib.TwistError):
+        ctx.twist_sample(2, 2, 255)
+    with pytest.raises(lib.TwistError):
+        ctx.twist_sample(2, 2, 513)
+    ctx.twist_sample(1, 1, 17, require_coverage=False).close()      # deployment relaxes the coverage bound
+
+
+# ------------------------------------------------------------------------------------------ extract / aggregate
+SMALL = {
+    "cfg1_f32": (si.CFG1, 2, 2, 256),
+    "gpt_bf16": (replace(si.CFG2, n_layers=2, vocab=1000, max_seq=64), 4, 3, 768),
+    "llama_bf16": (replace(si.CFG3, n_layers=2, d_model=512, n_heads=8, d_head=64, d_ff=1408, vocab=777, max_seq=64), 4, 4, 704),
+    "llama_overlap_S8": (replace(si.CFG4, n_layers=2, d_model=256, n_heads=8, d_head=32, d_ff=1000), 8, 4, 500),
+    "gpt_blocks_f32": (replace(si.CFG1, n_layers=3, d_ff=768, ffn_granule=64, vocab=50, max_seq=16), 3, 2, 5),
+    "ragged_f32": (si.ModelCfg(n_layers=2, d_model=36, n_heads=5, d_head=6, d_ff=70, ffn_granule=7, vocab=19, max_seq=8), 3, 2, 4),
+    "ragged_bf16": (si.ModelCfg(n_layers=1, d_model=100, n_heads=3, d_head=10, d_ff=99, ffn_granule=1, vocab=0, dtype="bf16"), 2, 2, 60),
+}
+
+
+def _setup(lib, name, seed=0, **kw):
+    cfg, S, hs, fs = SMALL[name]
+    full_np = si.make_weights(cfg, seed, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = _ctx(lib, cfg)
+    plan = ctx.twist_sample(S, hs, fs, seed=seed + 1, **kw)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, seed + 1,
+                        layer_shared=kw.get("layer_shared"), require_coverage=kw.get("require_coverage", True))
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    return cfg, S, full_np, full_t, ctx, plan, oplan, fw
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_extract_is_a_bit_exact_gather(lib, name):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name)
+    for s in range(S):
+        sub = ctx.twist_extract(plan, fw, s)
+        got = subnet_to_numpy(sub, cfg)
+        want = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        for l in range(cfg.n_layers):
+            for k, w in want["layers"][l].items():
+                assert got["layers"][l][k].shape == w.shape, (l, k)
+                assert np.array_equal(got["layers"][l][k], w), (name, s, l, k)
+        for k, w in want["globals"].items():
+            assert np.array_equal(got["globals"][k], w), k
+    torch.cuda.synchronize()
+
+
+def _perturb(cfg, sub, s, seed=5):
+    """Stand-in for local training: add N(0, 1e-3) noise to every subnet tensor, same on both sides."""
+    pert = {}
+    for l in range(cfg.n_layers):
+        for k in si.layer_shapes(cfg):
+            v = sub.twist_subnet_view(l, k)
+            n = si.perturbation(seed, f"{s}.{l}.{k}", tuple(v.shape))
+            v.add_(torch.tensor(n, dtype=torch.float64).to(v.dtype).cuda())
+    for k in si.global_shapes(cfg):
+        v = sub.twist_subnet_view(-1, k)
+        v.add_(torch.tensor(si.perturbation(seed, f"{s}.g.{k}", tuple(v.shape)), dtype=torch.float64).to(v.dtype).cuda())
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("drop", [False, True])
+def test_aggregate_matches_formula(lib, name, drop):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=3)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    for s, sub in enumerate(subs):
+        _perturb(cfg, sub, s)
+    use = list(range(S))
+    if drop:
+        use = use[1:] if S > 1 else use      # a worker that never reports back
+        use = use[::-1]                       # and an arbitrary order
+    sub_np = {s: subnet_to_numpy(subs[s], cfg) for s in use}
+    want = omove.aggregate(full_np, oplan, sub_np, cfg.d_head, cfg.ffn_granule)
+    ctx.twist_aggregate(plan, [subs[s] for s in use], fw)
+    got = model_to_numpy(full_t)
+    tol = 5e-3 if cfg.dtype == "bf16" else 1e-4
+    for l in range(cfg.n_layers):
+        for k, w in want["layers"][l].items():
+            g = got["layers"][l][k]
+            assert rel_fro(g, w) <= tol, (name, l, k, rel_fro(g, w))
+            if cfg.dtype == "bf16":
+                assert bf16_ulp_distance(g, si.to_bf16_grid(w)).max() <= 1, (l, k)
+            else:
+                np.testing.assert_allclose(g, w, rtol=3e-7, atol=1e-9)
+            # single-owner and ownerless parameters are exact copies
+            if k in omove.PARTITIONED:
+                kind, axis = omove.PARTITIONED[k]
+                q = cfg.d_head if kind == 0 else cfg.ffn_granule
+                cnt = np.zeros(oplan[l][kind]["n_full"], int)
+                for s in use:
+                    cnt[oplan[l][kind]["idx"][s]] += 1
+                e = np.repeat(cnt, q)
+                sel = e <= 1
+                gs, ws = (g[sel], w[sel]) if axis == 0 else (g[:, sel], w[:, sel])
+                assert np.array_equal(gs, ws), (l, k)
+    for k, w in want["globals"].items():
+        assert rel_fro(got["globals"][k], w) <= tol
+
+
+def test_untrained_partition_roundtrip_is_bit_exact(lib):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "gpt_bf16", seed=6)     # 12 = 4*3 heads, 3072 = 4*768
+    before = model_to_numpy(full_t)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    ctx.twist_aggregate(plan, subs, fw)
+    after = model_to_numpy(full_t)
+    for l in range(cfg.n_layers):
+        for k in before["layers"][l]:
+            assert np.array_equal(before["layers"][l][k], after["layers"][l][k]), k
+    for k in before["globals"]:
+        assert np.array_equal(before["globals"][k], after["globals"][k]), k
+
+
+def test_aggregate_is_deterministic(lib):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "llama_overlap_S8", seed=8)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    for s, sub in enumerate(subs):
+        _perturb(cfg, sub, s)
+    ctx.twist_aggregate(plan, subs, fw)
+    first = model_to_numpy(full_t)
+    for l, lw in enumerate(full_np["layers"]):          # reset and repeat
+        for k, v in lw.items():
+            full_t["layers"][l][k].copy_(torch.tensor(v, dtype=torch.float64))
+    ctx.twist_aggregate(plan, subs, fw)
+    second = model_to_numpy(full_t)
+    for l in range(cfg.n_layers):
+        for k in first["layers"][l]:
+            assert np.array_equal(first["layers"][l][k], second["layers"][l][k])
+
+
+def test_deployment_extract_leaves_uncovered_units_alone(lib):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "llama_bf16", seed=9, require_coverage=False)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    for s, sub in enumerate(subs):
+        _perturb(cfg, sub, s)
+    sub_np = {s: subnet_to_numpy(subs[s], cfg) for s in range(S)}
+    want = omove.aggregate(full_np, oplan, sub_np, cfg.d_head, cfg.ffn_granule)
+    ctx.twist_aggregate(plan, subs, fw)
+    got = model_to_numpy(full_t)
+    cnt = np.array(oplan[0][1]["count"])
+    assert (cnt == 0).any()                                 # some neurons really have no owner
+    for k in ("w_up", "w_gate"):
+        assert np.array_equal(got["layers"][0][k][cnt == 0], full_np["layers"][0][k][cnt == 0])
+    assert np.array_equal(got["layers"][0]["w_down"][:, cnt == 0], full_np["layers"][0]["w_down"][:, cnt == 0])
+    for k, w in want["layers"][0].items():
+        assert rel_fro(got["layers"][0][k], w) <= 5e-3
+
+
+# ------------------------------------------------------------------------------------------ full-size shapes
+def test_workload4_layer_shape_sampled_rows(lib):
+    """Two layers at the full Llama-7B layer shape, S = 8, in the launch configuration the benchmark times.
+    Weights are drawn on the device; the checker recomputes sampled rows and columns from the same values."""
+    cfg = replace(si.CFG4, n_layers=2)
+    S, hs, fs = 8, 16, 5504
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    layers = [{k: (torch.randn(shp, generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for k, shp in si.layer_shapes(cfg).items()}
+              for _ in range(cfg.n_layers)]
+    fw = lib.FullWeights(layers)
+    ctx = _ctx(lib, cfg)
+    plan = ctx.twist_sample(S, hs, fs, seed=11)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 11)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    rng = np.random.default_rng(0)
+    l = 1
+    heads = [oplan[l][0]["idx"][s] for s in range(S)]
+    units = [np.array(oplan[l][1]["idx"][s]) for s in range(S)]
+    # extract: sampled rows / columns of each partitioned tensor are exact copies
+    for s in (0, 5, 7):
+        e_head = omove.element_index(heads[s], cfg.d_head)
+        for name, e in (("wq", e_head), ("wv", e_head), ("w_up", units[s]), ("w_gate", units[s])):
+            rows = rng.integers(0, len(e), 16)
+            got = subs[s].twist_subnet_view(l, name)[torch.tensor(rows).cuda()]
+            assert torch.equal(got, layers[l][name][torch.tensor(e[rows]).cuda()]), (s, name)
+        for name, e in (("wo", e_head), ("w_down", units[s])):
+            rows = torch.tensor(rng.integers(0, cfg.d_model, 8)).cuda()
+            got = subs[s].twist_subnet_view(l, name)[rows]
+            assert torch.equal(got, layers[l][name][rows][:, torch.tensor(e).cuda()]), (s, name)
+    # train stand-in, then aggregate; check sampled rows against the formula evaluated in fp64
+    for s, sub in enumerate(subs):
+        for name in si.layer_shapes(cfg):
+            v = sub.twist_subnet_view(l, name)
+            v.add_((torch.randn(v.shape, generator=gen, device="cuda") * 1e-3).to(v.dtype))
+    old = {k: v.clone() for k, v in layers[l].items()}
+    ctx.twist_aggregate(plan, subs, fw)
+    for name in ("wk", "w_up", "wo", "w_down", "norm1_w"):
+        kind_axis = omove.PARTITIONED.get(name)
+        full_rows = rng.integers(0, layers[l][name].shape[0], 6)
+        for r in full_rows:
+            r = int(r)
+            got = to_numpy(layers[l][name][r])
+            if kind_axis is None:
+                want = sum(to_numpy(sub.twist_subnet_view(l, name)) for sub in subs)[r] / S
+            else:
+                kind, axis = kind_axis
+                q = cfg.d_head if kind == 0 else 1
+                num = np.zeros_like(got)
+                den = np.zeros_like(got)
+                for s, sub in enumerate(subs):
+                    e = omove.element_index(oplan[l][kind]["idx"][s], q)
+                    sv = sub.twist_subnet_view(l, name)
+                    if axis == 0:
+                        pos = np.nonzero(e == r)[0]
+                        if len(pos):
+                            num += to_numpy(sv[int(pos[0])])
+                            den += 1
+                    else:
+                        num[e] += to_numpy(sv[r])
+                        den[e] += 1
+                want = np.where(den > 0, num / np.maximum(den, 1), to_numpy(old[name][r]))
+            assert rel_fro(got, want) <= 5e-3, (name, r)
+            assert bf16_ulp_distance(got, si.to_bf16_grid(want)).max() <= 1, (name, r)
+    # counts: Alg. 1 covers every unit, and the counts add up
+    _, _, cnt = plan.twist_plan_view(l, 1)
+    assert int(cnt.min()) >= 1 and int(cnt.sum()) == S * fs
