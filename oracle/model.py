@@ -245,6 +245,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         dq = np.einsum("bhnm,bmhe->bnhe", ds, kh)
         dk = np.einsum("bhnm,bnhe->bmhe", ds, qh)
         if cfg.rope:
+            dq, dk = q("dact", dq), q("dact", dk)      # rounding point only; identity by default
             dq, dk = rope_apply(dq, cos, sin, -1.0), rope_apply(dk, cos, sin, -1.0)
         dq, dk, dv = (q("dact", t).reshape(T, Hs * dh) for t in (dq, dk, dv))
         hf_ = c["h"].reshape(T, -1)

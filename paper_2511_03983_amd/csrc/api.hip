@@ -431,8 +431,10 @@ extern "C" twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, co
     sub->adam_m = reinterpret_cast<float *>(p); p += fb;
     sub->adam_v = reinterpret_cast<float *>(p); p += fb;
   }
-  // padding between tensors must be defined (the optimizer sweeps whole slabs)
-  twist_status st = twist_launch_zero(ctx, sub->params, pb);
+  // The few elements of padding between tensors are never read by any kernel except the optimizer
+  // sweeps, whose results there are never used, so the weight slab is not cleared (clearing it would
+  // add a full extra write of the subnet).
+  twist_status st = TWIST_OK;
   MoveLaunch ml;
   std::memset(&ml, 0, sizeof ml);
   ml.sub_base[0] = sub->params;

@@ -1,0 +1,470 @@
+// Memory-bound kernels of the subnet training path: embedding, norms (Appendix A.1), rotary positions,
+// activations, losses, reductions for bias / gain gradients, and the local optimizer steps.
+// Activations and weights are fp32 or bf16 (template flag BF); all arithmetic is fp32.
+#include "nn.h"
+
+namespace {
+
+constexpr int kT = 256;
+
+template <int BF> struct El;
+template <> struct El<0> {
+  using T = float;
+  static __device__ __forceinline__ float ld(const void *p, int64_t i) { return static_cast<const float *>(p)[i]; }
+  static __device__ __forceinline__ void st(void *p, int64_t i, float v) { static_cast<float *>(p)[i] = v; }
+};
+template <> struct El<1> {
+  using T = uint16_t;
+  static __device__ __forceinline__ float ld(const void *p, int64_t i) {
+    return __uint_as_float((uint32_t) static_cast<const uint16_t *>(p)[i] << 16);
+  }
+  static __device__ __forceinline__ void st(void *p, int64_t i, float v) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) u = (u >> 16) | 0x40u;
+    else { u += 0x7fffu + ((u >> 16) & 1u); u >>= 16; }
+    static_cast<uint16_t *>(p)[i] = (uint16_t)u;
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// block-wide sum for kT threads; result valid in every thread
+__device__ __forceinline__ float block_sum(float v, float *sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+__device__ __forceinline__ float block_max(float v, float *sh) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+
+// ------------------------------------------------------------------------------------------- embedding
+template <int BF>
+__global__ __launch_bounds__(kT) void embed_fwd_kernel(const int32_t *tok, const void *E, const void *P, float *x, int N, int D, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  int64_t t = i / D;
+  int c = (int)(i - t * D);
+  float v = El<BF>::ld(E, (int64_t)tok[t] * D + c);
+  if (P) v += El<BF>::ld(P, (int64_t)(t % N) * D + c);
+  x[i] = v;
+}
+
+__global__ __launch_bounds__(kT) void embed_bwd_tok_kernel(const int32_t *tok, const float *dx, float *dE, int D, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  int64_t t = i / D;
+  int c = (int)(i - t * D);
+  atomicAdd(&dE[(int64_t)tok[t] * D + c], dx[i]);
+}
+
+__global__ __launch_bounds__(kT) void embed_bwd_pos_kernel(const float *dx, float *dP, int B, int N, int D) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;  // over N*D
+  if (i >= (int64_t)N * D) return;
+  float s = 0.f;
+  for (int b = 0; b < B; ++b) s += dx[(int64_t)b * N * D + i];
+  dP[i] = s;
+}
+
+template <int BF>
+__global__ __launch_bounds__(kT) void cast_in_kernel(const void *src, float *dst, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i < n) dst[i] = El<BF>::ld(src, i);
+}
+
+// ------------------------------------------------------------------------------------------- norms
+// one wave per row
+template <int BF, int RMS>
+__global__ __launch_bounds__(kT) void norm_fwd_kernel(const float *x, const void *w, const void *b, void *y, float *stats, int T, int D, float eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const float *xr = x + (int64_t)row * D;
+  float mean = 0.f;
+  if (!RMS) {
+    float s = 0.f;
+    for (int c = lane; c < D; c += 64) s += xr[c];
+    mean = wave_sum(s) / D;
+  }
+  float s2 = 0.f;
+  for (int c = lane; c < D; c += 64) { float d = xr[c] - mean; s2 += d * d; }
+  const float rstd = 1.0f / sqrtf(wave_sum(s2) / D + eps);
+  for (int c = lane; c < D; c += 64) {
+    float v = (xr[c] - mean) * rstd * El<BF>::ld(w, c);
+    if (b) v += El<BF>::ld(b, c);
+    El<BF>::st(y, (int64_t)row * D + c, v);
+  }
+  if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+}
+
+template <int BF, int RMS>
+__global__ __launch_bounds__(kT) void norm_bwd_dx_kernel(const void *dy, const float *x, const void *w, const float *stats, float *dx, int accumulate,
+                                                          void *dxb, int T, int D) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+  const float *xr = x + (int64_t)row * D;
+  float c1 = 0.f, c2 = 0.f;
+  for (int c = lane; c < D; c += 64) {
+    float dz = El<BF>::ld(dy, (int64_t)row * D + c) * El<BF>::ld(w, c);
+    float z = (xr[c] - mean) * rstd;
+    c1 += dz;
+    c2 += dz * z;
+  }
+  c1 = RMS ? 0.f : wave_sum(c1) / D;
+  c2 = wave_sum(c2) / D;
+  for (int c = lane; c < D; c += 64) {
+    float dz = El<BF>::ld(dy, (int64_t)row * D + c) * El<BF>::ld(w, c);
+    float z = (xr[c] - mean) * rstd;
+    float g = rstd * (dz - c1 - z * c2);
+    const int64_t i = (int64_t)row * D + c;
+    if (accumulate) g += dx[i];
+    dx[i] = g;
+    if (dxb) El<BF>::st(dxb, i, g);
+  }
+}
+
+constexpr int kChunkRows = 128;
+
+// partial[chunk][0][c] = sum over the chunk's rows of dy*z ; partial[chunk][1][c] = sum of dy
+template <int BF>
+__global__ __launch_bounds__(64) void norm_bwd_dw_kernel(const void *dy, const float *x, const float *stats, float *partial, int T, int D) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  const int chunk = blockIdx.y;
+  if (c >= D) return;
+  const int r0 = chunk * kChunkRows, r1 = min(r0 + kChunkRows, T);
+  float sw = 0.f, sb = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    float g = El<BF>::ld(dy, (int64_t)r * D + c);
+    float z = (x[(int64_t)r * D + c] - stats[2 * r]) * stats[2 * r + 1];
+    sw += g * z;
+    sb += g;
+  }
+  partial[((int64_t)chunk * 2) * D + c] = sw;
+  partial[((int64_t)chunk * 2 + 1) * D + c] = sb;
+}
+
+// out[c] = alpha * sum_k partial[k*stride + c]
+__global__ __launch_bounds__(kT) void reduce_partial_kernel(const float *partial, int64_t stride, int n_chunks, float alpha, float *out, int n) {
+  const int c = blockIdx.x * kT + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int k = 0; k < n_chunks; ++k) s += partial[(int64_t)k * stride + c];
+  out[c] = alpha * s;
+}
+
+template <int BF>
+__global__ __launch_bounds__(64) void colsum_kernel(const void *src, int64_t ld, float *partial, int T, int n) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  const int chunk = blockIdx.y;
+  if (c >= n) return;
+  const int r0 = chunk * kChunkRows, r1 = min(r0 + kChunkRows, T);
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += El<BF>::ld(src, (int64_t)r * ld + c);
+  partial[(int64_t)chunk * n + c] = s;
+}
+
+// ------------------------------------------------------------------------------------------- rotary
+__global__ __launch_bounds__(kT) void rope_table_kernel(float *tab, int N, int half, int dh, float theta) {
+  int i = blockIdx.x * kT + threadIdx.x;
+  if (i >= N * half) return;
+  int pos = i / half, f = i - pos * half;
+  double ang = (double)pos * pow((double)theta, -2.0 * (double)f / (double)dh);
+  tab[2 * i] = (float)cos(ang);
+  tab[2 * i + 1] = (float)sin(ang);
+}
+
+// q and k heads of a fused [T, 3*Hs*dh] buffer, in place; pair (i, i + dh/2)
+template <int BF>
+__global__ __launch_bounds__(kT) void rope_kernel(void *qkv, const float *tab, int N, int Hs, int dh, float sign, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;  // over T * 2Hs * half
+  if (i >= total) return;
+  const int half = dh / 2;
+  int f = (int)(i % half);
+  int64_t r = i / half;
+  int head = (int)(r % (2 * Hs));
+  int64_t t = r / (2 * Hs);
+  int pos = (int)(t % N);
+  const float c = tab[2 * (pos * half + f)], s = sign * tab[2 * (pos * half + f) + 1];
+  const int64_t base = t * (3 * (int64_t)Hs * dh) + (int64_t)head * dh + f;
+  float a = El<BF>::ld(qkv, base), b = El<BF>::ld(qkv, base + half);
+  El<BF>::st(qkv, base, a * c - b * s);
+  El<BF>::st(qkv, base + half, b * c + a * s);
+}
+
+// ------------------------------------------------------------------------------------------- activations
+__device__ __forceinline__ float gelu_tanh(float u) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  return 0.5f * u * (1.f + tanhf(k0 * (u + k1 * u * u * u)));
+}
+__device__ __forceinline__ float gelu_tanh_grad(float u) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  float t = tanhf(k0 * (u + k1 * u * u * u));
+  return 0.5f * (1.f + t) + 0.5f * u * (1.f - t * t) * k0 * (1.f + 3.f * k1 * u * u);
+}
+__device__ __forceinline__ float sigmoidf(float x) { return 1.f / (1.f + __expf(-x)); }
+
+template <int BF>
+__global__ __launch_bounds__(kT) void act_fwd_kernel(int act, const void *gu, void *a, int F, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  if (act == TWIST_ACT_SWIGLU) {
+    int64_t t = i / F;
+    int c = (int)(i - t * F);
+    float g = El<BF>::ld(gu, t * 2 * F + c), u = El<BF>::ld(gu, t * 2 * F + F + c);
+    El<BF>::st(a, i, g * sigmoidf(g) * u);
+  } else {
+    float u = El<BF>::ld(gu, i);
+    El<BF>::st(a, i, act == TWIST_ACT_RELU ? fmaxf(u, 0.f) : gelu_tanh(u));
+  }
+}
+
+template <int BF>
+__global__ __launch_bounds__(kT) void act_bwd_kernel(int act, const void *gu, const void *da, void *dgu, int F, int64_t total) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const float d = El<BF>::ld(da, i);
+  if (act == TWIST_ACT_SWIGLU) {
+    int64_t t = i / F;
+    int c = (int)(i - t * F);
+    float g = El<BF>::ld(gu, t * 2 * F + c), u = El<BF>::ld(gu, t * 2 * F + F + c);
+    float sg = sigmoidf(g);
+    El<BF>::st(dgu, t * 2 * F + F + c, d * g * sg);
+    El<BF>::st(dgu, t * 2 * F + c, d * u * (sg + g * sg * (1.f - sg)));
+  } else {
+    float u = El<BF>::ld(gu, i);
+    El<BF>::st(dgu, i, d * (act == TWIST_ACT_RELU ? (u > 0.f ? 1.f : 0.f) : gelu_tanh_grad(u)));
+  }
+}
+
+// ------------------------------------------------------------------------------------------- losses
+// one workgroup per row: logsumexp, row loss, then dlogits in place
+template <int BF>
+__global__ __launch_bounds__(kT) void ce_kernel(void *logits, int64_t ld, const int32_t *targets, float *rowloss, int V, float inv_T) {
+  __shared__ float sh[4];
+  const int64_t base = (int64_t)blockIdx.x * ld;
+  float m = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += kT) m = fmaxf(m, El<BF>::ld(logits, base + c));
+  m = block_max(m, sh);
+  float s = 0.f;
+  for (int c = threadIdx.x; c < V; c += kT) s += __expf(El<BF>::ld(logits, base + c) - m);
+  s = block_sum(s, sh);
+  const float lse = m + logf(s);
+  const int tgt = targets[blockIdx.x];
+  if (threadIdx.x == 0) rowloss[blockIdx.x] = lse - El<BF>::ld(logits, base + tgt);
+  __syncthreads();
+  for (int c = threadIdx.x; c < V; c += kT) {
+    float p = __expf(El<BF>::ld(logits, base + c) - lse);
+    El<BF>::st(logits, base + c, (p - (c == tgt ? 1.f : 0.f)) * inv_T);
+  }
+  // columns between V and the padded row stride are read (times zero weights) by the next projection
+  for (int c = V + threadIdx.x; c < ld; c += kT) El<BF>::st(logits, base + c, 0.f);
+}
+
+__global__ __launch_bounds__(kT) void mean_kernel(const float *v, int64_t n, float scale, float *out) {
+  __shared__ float sh[4];
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < n; i += kT) s += v[i];
+  s = block_sum(s, sh);
+  if (threadIdx.x == 0) *out = s * scale;
+}
+
+template <int BF>
+__global__ __launch_bounds__(kT) void mse_kernel(const float *x, const void *y, float *dx, void *dxb, float *partial, int64_t n, float two_over_n) {
+  __shared__ float sh[4];
+  float s = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT) {
+    float d = x[i] - El<BF>::ld(y, i);
+    s += d * d;
+    float g = d * two_over_n;
+    dx[i] = g;
+    El<BF>::st(dxb, i, g);
+  }
+  s = block_sum(s, sh);
+  if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+// ------------------------------------------------------------------------------------------- optimizers
+template <int BF>
+__global__ __launch_bounds__(kT) void sgd_kernel(void *params, float *master, const float *grads, int64_t n, float lr) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= n) return;
+  if (BF) {
+    float w = master[i] - lr * grads[i];
+    master[i] = w;
+    El<BF>::st(params, i, w);
+  } else {
+    static_cast<float *>(params)[i] -= lr * grads[i];
+  }
+}
+
+template <int BF>
+__global__ __launch_bounds__(kT) void adamw_kernel(void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,
+                                                    float lr, float b1, float b2, float eps, float wd, float inv_bc1, float inv_bc2) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= n) return;
+  const float g = grads[i];
+  const float mi = b1 * m[i] + (1.f - b1) * g;
+  const float vi = b2 * v[i] + (1.f - b2) * g * g;
+  m[i] = mi;
+  v[i] = vi;
+  float w = BF ? master[i] : static_cast<float *>(params)[i];
+  const float decay = i < n_decay ? wd : 0.f;
+  w -= lr * ((mi * inv_bc1) / (sqrtf(vi * inv_bc2) + eps) + decay * w);
+  if (BF) { master[i] = w; El<BF>::st(params, i, w); }
+  else static_cast<float *>(params)[i] = w;
+}
+
+__global__ __launch_bounds__(kT) void zero_f32_kernel(float *p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+inline dim3 grid1(int64_t n) { return dim3((unsigned)((n + kT - 1) / kT)); }
+
+}  // namespace
+
+#define LAUNCH_BF(kern, bf, grid, block, ...)                                             \
+  do {                                                                                    \
+    if (bf) hipLaunchKernelGGL((kern<1>), grid, block, 0, ctx->stream, __VA_ARGS__);      \
+    else hipLaunchKernelGGL((kern<0>), grid, block, 0, ctx->stream, __VA_ARGS__);         \
+    TW_HIP(ctx, hipGetLastError());                                                       \
+  } while (0)
+
+#define LAUNCH_BF2(kern, bf, flag, grid, block, ...)                                                  \
+  do {                                                                                                \
+    if (bf && flag) hipLaunchKernelGGL((kern<1, 1>), grid, block, 0, ctx->stream, __VA_ARGS__);       \
+    else if (bf) hipLaunchKernelGGL((kern<1, 0>), grid, block, 0, ctx->stream, __VA_ARGS__);          \
+    else if (flag) hipLaunchKernelGGL((kern<0, 1>), grid, block, 0, ctx->stream, __VA_ARGS__);        \
+    else hipLaunchKernelGGL((kern<0, 0>), grid, block, 0, ctx->stream, __VA_ARGS__);                  \
+    TW_HIP(ctx, hipGetLastError());                                                                   \
+  } while (0)
+
+twist_status twist_zero_f32(twist_ctx *ctx, float *p, int64_t n) {
+  if (n <= 0) return TWIST_OK;
+  hipLaunchKernelGGL(zero_f32_kernel, grid1(n), dim3(kT), 0, ctx->stream, p, n);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_embed_fwd(twist_ctx *ctx, int bf16, const int32_t *tok, const void *E, const void *P, float *x, int B, int N, int D, int) {
+  const int64_t total = (int64_t)B * N * D;
+  LAUNCH_BF(embed_fwd_kernel, bf16, grid1(total), dim3(kT), tok, E, P, x, N, D, total);
+  return TWIST_OK;
+}
+
+twist_status twist_embed_bwd(twist_ctx *ctx, const int32_t *tok, const float *dx, float *d_tok, float *d_pos, int B, int N, int D) {
+  const int64_t total = (int64_t)B * N * D;
+  hipLaunchKernelGGL(embed_bwd_tok_kernel, grid1(total), dim3(kT), 0, ctx->stream, tok, dx, d_tok, D, total);
+  TW_HIP(ctx, hipGetLastError());
+  if (d_pos) {
+    hipLaunchKernelGGL(embed_bwd_pos_kernel, grid1((int64_t)N * D), dim3(kT), 0, ctx->stream, dx, d_pos, B, N, D);
+    TW_HIP(ctx, hipGetLastError());
+  }
+  return TWIST_OK;
+}
+
+twist_status twist_cast_in(twist_ctx *ctx, int bf16, const void *src, float *dst, int64_t n) {
+  LAUNCH_BF(cast_in_kernel, bf16, grid1(n), dim3(kT), src, dst, n);
+  return TWIST_OK;
+}
+
+twist_status twist_norm_fwd(twist_ctx *ctx, int bf16, int rms, const float *x, const void *w, const void *b, void *y, float *stats, int T, int D, float eps) {
+  LAUNCH_BF2(norm_fwd_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), x, w, b, y, stats, T, D, eps);
+  return TWIST_OK;
+}
+
+static int n_chunks(int T) { return (T + kChunkRows - 1) / kChunkRows; }
+size_t twist_norm_partial_floats(int T, int D) { return (size_t)n_chunks(T) * 2 * D; }
+size_t twist_colsum_partial_floats(int T, int n) { return (size_t)n_chunks(T) * n; }
+
+twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
+                            int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D) {
+  // parameter gradients first: they read dy and x, which the dx pass leaves untouched
+  const int nc = n_chunks(T);
+  LAUNCH_BF(norm_bwd_dw_kernel, bf16, dim3((D + 63) / 64, nc), dim3(64), dy, x, stats, partial, T, D);
+  hipLaunchKernelGGL(reduce_partial_kernel, grid1(D), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+  TW_HIP(ctx, hipGetLastError());
+  if (db) {
+    hipLaunchKernelGGL(reduce_partial_kernel, grid1(D), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
+    TW_HIP(ctx, hipGetLastError());
+  }
+  LAUNCH_BF2(norm_bwd_dx_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), dy, x, w, stats, dx, accumulate, dxb, T, D);
+  return TWIST_OK;
+}
+
+twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int n) {
+  const int nc = n_chunks(T);
+  LAUNCH_BF(colsum_kernel, bf16, dim3((n + 63) / 64, nc), dim3(64), src, ld, partial, T, n);
+  hipLaunchKernelGGL(reduce_partial_kernel, grid1(n), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+// rotary table lives at the start of `qkv`-independent scratch handed in by the caller through twist_rope_table
+twist_status twist_rope_table(twist_ctx *ctx, float *tab, int N, int dh, float theta) {
+  const int half = dh / 2;
+  hipLaunchKernelGGL(rope_table_kernel, grid1((int64_t)N * half), dim3(kT), 0, ctx->stream, tab, N, half, dh, theta);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_rope_apply(twist_ctx *ctx, int bf16, void *qkv, const float *tab, int B, int N, int Hs, int dh, float sign) {
+  const int64_t total = (int64_t)B * N * 2 * Hs * (dh / 2);
+  LAUNCH_BF(rope_kernel, bf16, grid1(total), dim3(kT), qkv, tab, N, Hs, dh, sign, total);
+  return TWIST_OK;
+}
+
+twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F) {
+  const int64_t total = (int64_t)T * F;
+  LAUNCH_BF(act_fwd_kernel, bf16, grid1(total), dim3(kT), act, gu, a, F, total);
+  return TWIST_OK;
+}
+
+twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F) {
+  const int64_t total = (int64_t)T * F;
+  LAUNCH_BF(act_bwd_kernel, bf16, grid1(total), dim3(kT), act, gu, da, dgu, F, total);
+  return TWIST_OK;
+}
+
+twist_status twist_ce_fwd_bwd(twist_ctx *ctx, int bf16, void *logits, int64_t ld, const int32_t *targets, float *rowloss, float *loss, int T, int V) {
+  LAUNCH_BF(ce_kernel, bf16, dim3(T), dim3(kT), logits, ld, targets, rowloss, V, 1.f / (float)T);
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kT), 0, ctx->stream, rowloss, (int64_t)T, 1.f / (float)T, loss);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_mse_fwd_bwd(twist_ctx *ctx, int bf16, const float *x, const void *y, float *dx, void *dxb, float *partial, float *loss, int64_t n) {
+  const int blocks = (int)std::min<int64_t>((n + kT - 1) / kT, 1024);
+  LAUNCH_BF(mse_kernel, bf16, dim3(blocks), dim3(kT), x, y, dx, dxb, partial, n, 2.f / (float)n);
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kT), 0, ctx->stream, partial, (int64_t)blocks, 1.f / (float)n, loss);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_sgd(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, int64_t n, float lr) {
+  LAUNCH_BF(sgd_kernel, bf16, grid1(n), dim3(kT), params, master, grads, n, lr);
+  return TWIST_OK;
+}
+
+twist_status twist_adamw(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,
+                         float lr, float b1, float b2, float eps, float wd, int64_t step) {
+  const double bc1 = 1.0 - pow((double)b1, (double)step), bc2 = 1.0 - pow((double)b2, (double)step);
+  LAUNCH_BF(adamw_kernel, bf16, grid1(n), dim3(kT), params, master, grads, m, v, n, n_decay, lr, b1, b2, eps, wd, (float)(1.0 / bc1), (float)(1.0 / bc2));
+  return TWIST_OK;
+}

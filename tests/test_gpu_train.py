@@ -1,0 +1,201 @@
+"""GPU parity of twist_subnet_fwd_bwd / twist_subnet_step against the CPU checker, through the C ABI.
+
+Tolerances (relative Frobenius error): 1e-4 on fp32 paths, 5e-3 on bf16-in / fp32-accumulate paths.
+
+bf16 models store every activation and activation gradient in bf16.  Each such rounding perturbs a tensor by
+about 2^-9/sqrt(3) = 1.1e-3 (rms, relative), and random-sign dot products pass that on undiminished, so the
+storage format alone puts the result 4e-3 .. 7e-3 away from exact arithmetic after one layer.  The bf16 gates
+therefore are:
+  * against the checker run with its rounding hook (same tensors snapped to bf16): <= 5e-3 for one layer,
+    <= 5e-3 * sqrt(L) for L layers (a rounding that flips changes everything downstream of it, so the two
+    implementations decorrelate by an independent amount per layer);
+  * against the exact fp64 checker: no further than the rounding-emulating checker is, plus 5e-3
+    (the kernels add no error beyond the storage format's own).
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from helpers import rel_fro, subnet_to_numpy, to_device, to_numpy
+from oracle import model as omodel, move as omove, optim as ooptim
+from oracle.sample import sample_plan
+
+pytestmark = pytest.mark.gpu
+GRAD = 1
+
+
+def _round_hook(tag, a):
+    return si.to_bf16_grid(a)
+
+
+CASES = {
+    # name: (cfg, S, heads_sub, ffn_sub, B, N)
+    "cfg1_block_f32": (si.CFG1, 2, 2, 256, 4, 64),
+    "gpt_f32": (si.ModelCfg(n_layers=2, d_model=96, n_heads=6, d_head=16, d_ff=200, vocab=301, max_seq=40), 3, 3, 100, 3, 37),
+    "llama_f32": (si.ModelCfg(arch="llama", n_layers=2, d_model=64, n_heads=4, d_head=16, d_ff=176, vocab=259, max_seq=48, act="swiglu",
+                              norm="rms", has_bias=False, tied_head=False, rope=True), 2, 2, 88, 2, 48),
+    "ragged_f32": (si.ModelCfg(n_layers=1, d_model=36, n_heads=5, d_head=6, d_ff=70, ffn_granule=7, vocab=19, max_seq=9), 2, 3, 6, 2, 9),
+    "gpt_bf16": (replace(si.CFG2, n_layers=2, d_model=256, n_heads=4, d_head=64, d_ff=1024, vocab=1003, max_seq=192), 2, 2, 512, 2, 192),
+    "llama_bf16": (replace(si.CFG3, n_layers=2, d_model=256, n_heads=4, d_head=128, d_ff=704, vocab=517, max_seq=256), 2, 2, 352, 1, 256),
+    "gpt_bf16_1l": (replace(si.CFG2, n_layers=1, d_model=256, n_heads=4, d_head=64, d_ff=1024, vocab=1003, max_seq=192), 2, 2, 512, 2, 192),
+    "llama_bf16_1l": (replace(si.CFG3, n_layers=1, d_model=256, n_heads=4, d_head=128, d_ff=704, vocab=517, max_seq=256), 2, 2, 352, 1, 256),
+    "block_llama_bf16": (replace(si.CFG4, n_layers=1, d_model=256, n_heads=4, d_head=64, d_ff=512, max_seq=128), 2, 2, 256, 2, 128),
+}
+
+
+def _data(cfg, B, N, seed):
+    if cfg.vocab:
+        t = si.tokens_uniform(cfg.vocab, B, N, seed)
+        x, y = t[:, :-1].copy(), t[:, 1:].copy()
+        return x, y, torch.tensor(x).cuda(), torch.tensor(y).cuda()
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    x, y = si.activations(cfg, B, N, seed, "x"), si.activations(cfg, B, N, seed, "y")
+    return x, y, torch.tensor(x, dtype=torch.float64).to(dt).cuda(), torch.tensor(y, dtype=torch.float64).to(dt).cuda()
+
+
+def _setup(lib, name, seed=0, store=1):
+    cfg, S, hs, fs, B, N = CASES[name]
+    full_np = si.make_weights(cfg, seed, std=0.05 if cfg.dtype == "f32" else 0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=seed + 1)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, seed + 1)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    return cfg, S, B, N, full_np, full_t, ctx, plan, oplan, fw
+
+
+def _compare_grads(cfg, got, want, tol, tag):
+    worst = 0.0
+    for l in range(cfg.n_layers):
+        for k, w in want["layers"][l].items():
+            if k == "bk":
+                # softmax is invariant to a shift of all keys, so this gradient is exactly zero in exact
+                # arithmetic: compare its size with the query-bias gradient instead of with itself
+                assert np.linalg.norm(got["layers"][l][k] - w) <= 10 * tol * np.linalg.norm(want["layers"][l]["bq"]), (tag, l, k)
+                continue
+            e = rel_fro(got["layers"][l][k], w)
+            worst = max(worst, e)
+            assert e <= tol, (tag, l, k, e)
+    for k, w in want["globals"].items():
+        e = rel_fro(got["globals"][k], w)
+        worst = max(worst, e)
+        assert e <= tol, (tag, k, e)
+    return worst
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_fwd_bwd_matches_oracle(lib, name):
+    cfg, S, B, N, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name)
+    x_np, y_np, x, y = _data(cfg, B, N, 3)
+    loss = torch.zeros(1, device="cuda")
+    bf = cfg.dtype == "bf16"
+    tol = 5e-3 if bf else 1e-4
+    for s in range(S):
+        sub = ctx.twist_extract(plan, fw, s, store=lib.STORE_GRADS)
+        ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        torch.cuda.synchronize()
+        osub = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        got = subnet_to_numpy(sub, cfg, GRAD)
+        oloss, ograds = omodel.forward_backward(cfg, osub, x_np, y_np)
+        assert abs(loss.item() - oloss) <= tol * abs(oloss), (loss.item(), oloss)
+        if bf:
+            # same rounding points as the library's bf16 storage
+            rloss, rgrads = omodel.forward_backward(cfg, osub, x_np, y_np, q=_round_hook)
+            assert abs(loss.item() - rloss) <= tol * abs(rloss)
+            _compare_grads(cfg, got, rgrads, tol * np.sqrt(cfg.n_layers), name + "/rounded")
+            fmt_err = _compare_grads(cfg, rgrads, ograds, 1.0, name + "/format")      # the storage format's own error
+            worst = _compare_grads(cfg, got, ograds, fmt_err + tol, name + "/exact")
+            print(f"{name} s={s}: worst rel. error vs exact fp64 checker {worst:.2e} (format alone {fmt_err:.2e})")
+        else:
+            _compare_grads(cfg, got, ograds, tol, name)
+
+
+@pytest.mark.parametrize("name,opt", [("cfg1_block_f32", "sgd"), ("llama_f32", "adamw"), ("llama_bf16", "adamw"), ("gpt_bf16", "sgd")])
+def test_local_steps_then_aggregate(lib, name, opt):
+    """extract -> a few local steps -> aggregate, end to end against the checker."""
+    cfg, S, B, N, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=4, store=2)
+    bf = cfg.dtype == "bf16"
+    hook = _round_hook if bf else (lambda t, a: a)
+    steps = 3 if opt == "adamw" else 1
+    lr = 1e-2 if opt == "sgd" else 1e-3
+    loss = torch.zeros(1, device="cuda")
+    subs, osubs = [], []
+    for s in range(S):
+        sub = ctx.twist_extract(plan, fw, s, store=lib.STORE_ADAMW)
+        ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        osub = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        master = {"layers": [dict(lw) for lw in osub["layers"]], "globals": dict(osub["globals"])}   # fp64 master copy
+        state = ooptim.adamw_init(master)
+        for it in range(steps):
+            x_np, y_np, x, y = _data(cfg, B, N, 10 * s + it)
+            ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+            if opt == "sgd":
+                ctx.twist_subnet_step(sub, lib.OPT_SGD, lr=lr)
+            else:
+                ctx.twist_subnet_step(sub, lib.OPT_ADAMW, lr=lr, weight_decay=0.01)
+            _, og = omodel.forward_backward(cfg, osub, x_np, y_np, q=hook)
+            og = {"layers": og["layers"], "globals": og["globals"]}
+            if opt == "sgd":
+                ooptim.sgd_step(master, og, lr)
+            else:
+                ooptim.adamw_step(master, og, state, lr=lr, weight_decay=0.01)
+            # the model the next step runs on is the master copy at the storage precision
+            osub = {"layers": [{k: (si.to_bf16_grid(v) if bf else v) for k, v in lw.items()} for lw in master["layers"]],
+                    "globals": {k: (si.to_bf16_grid(v) if bf else v) for k, v in master["globals"].items()}}
+        got = subnet_to_numpy(sub, cfg)
+        # compare the UPDATE (trained - extracted), which is what the steps computed
+        base = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        for l in range(cfg.n_layers):
+            for k, w in osub["layers"][l].items():
+                if k == "bk":
+                    continue                      # zero gradient (see _compare_grads); AdamW turns its noise into +-lr
+                if bf:
+                    assert rel_fro(got["layers"][l][k], w) <= 5e-3, (s, l, k)
+                else:
+                    # the trained weights to fp32 accuracy; the update itself only as far as fp32 storage of
+                    # w - lr*g resolves it (an ulp of a 0.05-sized weight is 4e-9, the updates are ~1e-6)
+                    assert rel_fro(got["layers"][l][k], w) <= 1e-4, (s, l, k)
+                    if opt == "adamw":
+                        continue      # m/sqrt(v) is ill-conditioned where a gradient entry is itself rounding noise
+                    du, dw = got["layers"][l][k] - base["layers"][l][k], w - base["layers"][l][k]
+                    ulp_noise = 1.2e-7 * np.abs(w).max() / max(np.linalg.norm(dw) / np.sqrt(dw.size), 1e-30)
+                    assert rel_fro(du, dw) <= 1e-4 + ulp_noise, (s, l, k, rel_fro(du, dw), ulp_noise)
+        subs.append(sub)
+        osubs.append(osub)
+    ctx.twist_aggregate(plan, subs, fw)
+    want = omove.aggregate(full_np, oplan, osubs, cfg.d_head, cfg.ffn_granule)
+    tol = 5e-3 if bf else 1e-4
+    for l in range(cfg.n_layers):
+        for k, w in want["layers"][l].items():
+            assert rel_fro(to_numpy(full_t["layers"][l][k]), w) <= tol, (l, k)
+    for k, w in want["globals"].items():
+        assert rel_fro(to_numpy(full_t["globals"][k]), w) <= tol, k
+
+
+def test_scale_mode_none_and_shape_errors(lib):
+    cfg, S, hs, fs, B, N = CASES["gpt_f32"]
+    full_np = si.make_weights(cfg, 1, std=0.05, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=2, scale_mode=lib.SCALE_NONE)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 2)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    sub = ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS)
+    x_np, y_np, x, y = _data(cfg, B, N, 3)
+    ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+    oloss, _ = omodel.forward_backward(cfg, omove.extract(full_np, oplan, 0, cfg.d_head), x_np, y_np, scale_mode=False)
+    assert abs(loss.item() - oloss) <= 1e-4 * oloss
+    with pytest.raises(lib.TwistError):                      # workspace too small
+        ctx.twist_subnet_fwd_bwd(sub, x, y, ws[:1024], loss)
+    with pytest.raises(lib.TwistError):                      # no gradient storage
+        ctx.twist_subnet_fwd_bwd(ctx.twist_extract(plan, fw, 1), x, y, ws, loss)
+    with pytest.raises(lib.TwistError):                      # AdamW without moment buffers
+        ctx.twist_subnet_step(sub, lib.OPT_ADAMW)
+    with pytest.raises(lib.TwistError):                      # sequence longer than max_seq
+        ctx.twist_workspace_bytes(sub, 1, cfg.max_seq + 1)
