@@ -186,6 +186,13 @@ TWIST_API twist_status twist_subnet_step(twist_ctx *ctx, twist_subnet *sub, cons
 TWIST_API twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, twist_subnet *const *subs, int32_t n_subs,
                              const twist_full_weights *inout);
 
+/* Measurement aid for benchmarks (not part of the method): while enabled, every projection (GEMM) launch on
+ * this ctx is bracketed by two HIP events on the ctx's stream.  twist_profile_gemm_read synchronises the
+ * stream, returns the number of launches, their summed duration in milliseconds and their summed algorithmic
+ * floating-point operations (2 M N K each) since enabling, and resets the counters. */
+TWIST_API twist_status twist_profile_gemm(twist_ctx *ctx, int32_t enable);
+TWIST_API twist_status twist_profile_gemm_read(twist_ctx *ctx, int64_t *launches, double *ms, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

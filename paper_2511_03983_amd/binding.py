@@ -80,6 +80,8 @@ _SIGS = {
     "twist_subnet_fwd_bwd": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
+    "twist_profile_gemm": ([_vp, _i32], _i32),
+    "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
 }
 for _name, (_args, _res) in _SIGS.items():
     _f = getattr(lib, _name)          # AttributeError here = the library lacks a declared entry point
@@ -159,6 +161,16 @@ class Context:
     def twist_aggregate(self, plan: "Plan", subs, full: "FullWeights") -> None:
         arr = (_vp * len(subs))(*[s.h for s in subs])
         _check(lib.twist_aggregate(self.h, plan.h, arr, len(subs), C.byref(full.c)), self.h)
+
+
+    def twist_profile_gemm(self, enable: bool) -> None:
+        _check(lib.twist_profile_gemm(self.h, int(enable)), self.h)
+
+    def twist_profile_gemm_read(self):
+        """(launches, milliseconds, algorithmic flops) of the projection kernels since enabling."""
+        n, ms, fl = C.c_int64(), C.c_double(), C.c_double()
+        _check(lib.twist_profile_gemm_read(self.h, C.byref(n), C.byref(ms), C.byref(fl)), self.h)
+        return n.value, ms.value, fl.value
 
 
 class Plan:

@@ -42,7 +42,11 @@ extern "C" twist_status twist_create(const twist_model_desc *desc, void *hip_str
   return TWIST_OK;
 }
 
-extern "C" void twist_destroy(twist_ctx *ctx) { delete ctx; }
+extern "C" void twist_destroy(twist_ctx *ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  delete ctx;
+}
 
 // ------------------------------------------------------------------------------------------------ generator
 namespace {

@@ -206,6 +206,20 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
                         int64_t ldc, const GemmEpilogue &e) {
   if (M <= 0 || N <= 0 || K <= 0) return TWIST_OK;
+  hipEvent_t ev_stop = nullptr;
+  if (ctx->prof_gemm) {
+    hipEvent_t ev_start;
+    TW_HIP(ctx, hipEventCreate(&ev_start));
+    TW_HIP(ctx, hipEventCreate(&ev_stop));
+    ctx->prof_events.push_back(ev_start);
+    ctx->prof_events.push_back(ev_stop);
+    ctx->prof_flops += 2.0 * M * N * K;
+    TW_HIP(ctx, hipEventRecord(ev_start, ctx->stream));
+  }
+  struct StopRecorder {  // records the closing event on every return path
+    twist_ctx *c; hipEvent_t e;
+    ~StopRecorder() { if (e) (void)hipEventRecord(e, c->stream); }
+  } stop_recorder{ctx, ev_stop};
   Ep ep{e.alpha, e.bias, e.residual, e.out, e.out_f32, ldc};
   static const bool no_mfma = getenv("TWIST_NO_MFMA") != nullptr;
   // 16-byte chunks along k must not straddle the end of an operand row.  For y = x W with a ragged K the
@@ -235,5 +249,33 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   if (bf16) hipLaunchKernelGGL(gemm_plain_kernel<1>, grid, block, 0, ctx->stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
   else hipLaunchKernelGGL(gemm_plain_kernel<0>, grid, block, 0, ctx->stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
   TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_profile_gemm(twist_ctx *ctx, int32_t enable) {
+  if (!ctx) TW_FAIL(nullptr, TWIST_EINVAL, "twist_profile_gemm: null ctx");
+  TW_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  ctx->prof_events.clear();
+  ctx->prof_flops = 0.0;
+  ctx->prof_gemm = enable != 0;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_profile_gemm_read(twist_ctx *ctx, int64_t *launches, double *ms, double *flops) {
+  if (!ctx || !launches || !ms || !flops) TW_FAIL(ctx, TWIST_EINVAL, "twist_profile_gemm_read: null argument");
+  TW_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double total = 0.0;
+  for (size_t i = 0; i + 1 < ctx->prof_events.size(); i += 2) {
+    float t = 0.f;
+    TW_HIP(ctx, hipEventElapsedTime(&t, ctx->prof_events[i], ctx->prof_events[i + 1]));
+    total += t;
+  }
+  *launches = (int64_t)(ctx->prof_events.size() / 2);
+  *ms = total;
+  *flops = ctx->prof_flops;
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  ctx->prof_events.clear();
+  ctx->prof_flops = 0.0;
   return TWIST_OK;
 }

@@ -62,6 +62,10 @@ struct twist_ctx {
   twist_model_desc d;
   hipStream_t stream = nullptr;
   mutable std::string err;
+  // optional per-launch timing of the projection kernels (see twist_profile_gemm)
+  bool prof_gemm = false;
+  std::vector<hipEvent_t> prof_events;  // (start, stop) pairs
+  double prof_flops = 0.0;
   int esize() const { return d.dtype == TWIST_BF16 ? 2 : 4; }
   int n_ffn_units() const { return d.d_ff / d.ffn_granule; }
 };
