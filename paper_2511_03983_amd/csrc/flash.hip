@@ -1,13 +1,386 @@
-// Tiled MFMA attention kernels for bf16 models (placeholder: reports "not handled" so that the plain
-// kernels run).
+// Tiled causal attention for bf16 models on the matrix cores (v_mfma_f32_32x32x16_bf16), forward and backward.
+//
+// All kernels work on the fused [T, 3*Hs*dh] q|k|v buffer, d_head 64 or 128, N a multiple of 128.
+// Layout facts used throughout (32x32x16 MFMA, wave of 64 lanes, g = lane/32, c = lane%32):
+//   A operand (M x K): lane supplies row c, k = 8g .. 8g+7          B operand (K x N): lane supplies column c, same k
+//   D (32 x 32):       lane holds column c, register r holds row 8*(r/4) + 4g + r%4
+// Scores are formed TRANSPOSED, S^T = K Q^T, so that a lane owns one query column: the softmax statistics of a
+// query live in one lane (plus its partner lane^32), and the probability tile can be fed straight back as the
+// B operand of the next product by renaming the contraction index: MFMA k-slot (g, i) of step t stands for row
+// 16t + 8*(i/4) + 4g + i%4 of the tile, which is exactly where register 8t+i of the D layout sits.
+// Operands whose contraction index is the slow axis in memory (V in P.V, K in dS.K, Q and dO in the dK/dV
+// products) stay row-major in LDS and are read with the transposing LDS load ds_read_tr16_b64, which hands
+// each lane 4 consecutive contraction rows of one column.
+//
+// delta_i = sum_j p_ij dp_ij is recomputed from p and dp in a first pass of the dQ kernel rather than taken
+// from the rounded output (see attention.hip).
 #include "nn.h"
 
-twist_status twist_attention_fwd_mfma(twist_ctx *, const void *, void *, float *, int, int, int, int, bool *done) {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ uint32_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);  // finite inputs only
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return f2bf(a) | (f2bf(b) << 16); }
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int r0) {
+  u32x4 u = {pack2(v[r0], v[r0 + 1]), pack2(v[r0 + 2], v[r0 + 3]), pack2(v[r0 + 4], v[r0 + 5]), pack2(v[r0 + 6], v[r0 + 7])};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ bf16x8 lds_frag(const uint16_t *p) { return *reinterpret_cast<const bf16x8 *>(p); }
+
+// 8 contraction rows (two groups of 4) of one column, from a row-major LDS tile: rows row0..row0+3 and row0+8..row0+11
+__device__ __forceinline__ bf16x8 lds_frag_tr(const uint16_t *tile, int ld, int row0, int col0) {
+  const int s = threadIdx.x & 15;
+  const uint16_t *p = tile + (row0 + (s >> 2)) * ld + col0 + 4 * (s & 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 8 * ld));
+  s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// cooperative copy of a [ROWS][DH] tile (row stride ldg in memory) into LDS with row stride ldl; 256 threads
+template <int ROWS, int DH>
+__device__ __forceinline__ void load_tile(uint16_t *lds, int ldl, const uint16_t *g, int64_t ldg) {
+  constexpr int CPR = DH / 8, TOTAL = ROWS * CPR;
+#pragma unroll
+  for (int i = 0; i < TOTAL / 256; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    const int r = c / CPR, k = (c % CPR) * 8;
+    *reinterpret_cast<u32x4 *>(lds + r * ldl + k) = *reinterpret_cast<const u32x4 *>(g + (int64_t)r * ldg + k);
+  }
+}
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// ------------------------------------------------------------------------------------------- forward
+// grid: (N/128) * B * Hs workgroups of 4 waves; wave w owns query rows [qb*128 + 32w, +32)
+template <int DH>
+__global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uint16_t *o, float *lse, int N, int Hs, float scale) {
+  constexpr int KS = DH / 16, MT = DH / 32, LDK = DH + 8, LDV = DH + 16;
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LDK];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LDV];
+  const int nqb = N / 128;
+  const int qb = nqb - 1 - (int)(blockIdx.x % nqb);  // long rows first
+  const int bh = blockIdx.x / nqb, b = bh / Hs, h = bh % Hs;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
+  const uint16_t *kp = qp + HD, *vp = qp + 2 * HD;
+  const int q0 = qb * 128 + wave * 32, q = q0 + c;
+  const float sc = scale * kLog2e;
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)q * ld + ks * 16 + g * 8);
+  f32x16 oacc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int n_tiles = (qb + 1) * 2;
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    __syncthreads();
+    load_tile<64, DH>(Ks, LDK, kp + (int64_t)kt * 64 * ld, ld);
+    load_tile<64, DH>(Vs, LDV, vp + (int64_t)kt * 64 * ld, ld);
+    __syncthreads();
+    if (kt * 64 > q0 + 31) continue;  // whole tile is in this wave's future
+    f32x16 s[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LDK + ks * 16 + g * 8), qf[ks], s[mt]);
+    const bool diag = kt * 64 + 63 > q0;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        float v = s[mt][r] * sc;
+        if (diag && kv > q) v = -INFINITY;
+        s[mt][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and belongs to the first tile
+    const float alpha = exp2f(m - mn);
+    float sum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[mt][r] - mn);
+        s[mt][r] = p;
+        sum += p;
+      }
+    l = l * alpha + sum;
+    m = mn;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    // O^T[dh][q] += V^T[dh][kv] P^T[kv][q]
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pf = pack8(s[mt], 8 * t);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          oacc[i] = MFMA(lds_frag_tr(Vs, LDV, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), pf, oacc[i]);
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  const float inv = 1.f / l;
+  uint16_t *op = o + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 w = {pack2(oacc[i][4 * j] * inv, oacc[i][4 * j + 1] * inv), pack2(oacc[i][4 * j + 2] * inv, oacc[i][4 * j + 3] * inv)};
+      *reinterpret_cast<u32x2 *>(op + i * 32 + 8 * j + 4 * g) = w;
+    }
+  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
+}
+
+// ------------------------------------------------------------------------------------------- backward: dQ (and delta)
+// Same decomposition as the forward kernel.  Pass 1 accumulates delta_q = sum_kv p dp; pass 2 forms
+// dS^T = p (dp - delta) scale and dQ^T[dh][q] += K^T[dh][kv] dS^T[kv][q].
+template <int DH>
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, float *delta, uint16_t *dqkv,
+                                                           int N, int Hs, float scale) {
+  constexpr int KS = DH / 16, MT = DH / 32, LD = DH + 16;
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LD];
+  const int nqb = N / 128;
+  const int qb = nqb - 1 - (int)(blockIdx.x % nqb);
+  const int bh = blockIdx.x / nqb, b = bh / Hs, h = bh % Hs;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
+  const uint16_t *kp = qp + HD, *vp = qp + 2 * HD;
+  const int q0 = qb * 128 + wave * 32, q = q0 + c;
+  const float sc = scale * kLog2e;
+  const float L2 = lse[((int64_t)b * Hs + h) * N + q] * kLog2e;
+
+  bf16x8 qf[KS], gf[KS];
+  const uint16_t *gp = dout + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)q * ld + ks * 16 + g * 8);
+    gf[ks] = *reinterpret_cast<const bf16x8 *>(gp + ks * 16 + g * 8);
+  }
+  f32x16 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  float dl = 0.f;
+  const int n_tiles = (qb + 1) * 2;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int kt = 0; kt < n_tiles; ++kt) {
+      __syncthreads();
+      load_tile<64, DH>(Ks, LD, kp + (int64_t)kt * 64 * ld, ld);
+      load_tile<64, DH>(Vs, LD, vp + (int64_t)kt * 64 * ld, ld);
+      __syncthreads();
+      if (kt * 64 > q0 + 31) continue;
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LD + ks * 16 + g * 8), qf[ks], s[mt]);
+          dp[mt] = MFMA(lds_frag(Vs + (mt * 32 + c) * LD + ks * 16 + g * 8), gf[ks], dp[mt]);
+        }
+      const bool diag = kt * 64 + 63 > q0;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          float p = exp2f(s[mt][r] * sc - L2);
+          if (diag && kv > q) p = 0.f;
+          if (pass == 0) dl += p * dp[mt][r];
+          else s[mt][r] = p * (dp[mt][r] - dl) * scale;
+        }
+      if (pass == 0) continue;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 df = pack8(s[mt], 8 * t);
+#pragma unroll
+          for (int i = 0; i < MT; ++i)
+            acc[i] = MFMA(lds_frag_tr(Ks, LD, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), df, acc[i]);
+        }
+    }
+    if (pass == 0) {
+      dl += __shfl_xor(dl, 32, 64);
+      if (g == 0) delta[((int64_t)b * Hs + h) * N + q] = dl;
+    }
+  }
+  uint16_t *op = dqkv + ((int64_t)b * N + q) * ld + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 w = {pack2(acc[i][4 * j], acc[i][4 * j + 1]), pack2(acc[i][4 * j + 2], acc[i][4 * j + 3])};
+      *reinterpret_cast<u32x2 *>(op + i * 32 + 8 * j + 4 * g) = w;
+    }
+}
+
+// ------------------------------------------------------------------------------------------- backward: dK, dV
+// grid: (N/128) * B * Hs; wave w owns key/value rows [kb*128 + 32w, +32) and walks the query tiles at or below the
+// diagonal.  S[q][kv] = Q K^T and dP = dO V^T put a key column in each lane; P and dS then are the B operands of
+// dV^T[dh][kv] += dO^T[dh][q] P[q][kv]  and  dK^T[dh][kv] += Q^T[dh][q] dS[q][kv].
+template <int DH>
+__global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
+                                                            uint16_t *dqkv, int N, int Hs, float scale) {
+  constexpr int KS = DH / 16, MT = DH / 32, LD = DH + 16;
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * LD];
+  __shared__ __attribute__((aligned(16))) float Ls[64], Ds[64];
+  const int nkb = N / 128;
+  const int kb = blockIdx.x % nkb;  // early key blocks see the most queries: they come first
+  const int bh = blockIdx.x / nkb, b = bh / Hs, h = bh % Hs;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
+  const uint16_t *gp = dout + (int64_t)b * N * HD + (int64_t)h * DH;
+  const int k0 = kb * 128 + wave * 32, kv = k0 + c;
+  const float sc = scale * kLog2e;
+  const float *lse_b = lse + ((int64_t)b * Hs + h) * N, *del_b = delta + ((int64_t)b * Hs + h) * N;
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8 *>(qp + HD + (int64_t)kv * ld + ks * 16 + g * 8);
+    vf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 2 * HD + (int64_t)kv * ld + ks * 16 + g * 8);
+  }
+  f32x16 dk[MT], dv[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+
+  for (int qt = kb * 2; qt < N / 64; ++qt) {
+    __syncthreads();
+    load_tile<64, DH>(Qs, LD, qp + (int64_t)qt * 64 * ld, ld);
+    load_tile<64, DH>(Gs, LD, gp + (int64_t)qt * 64 * HD, HD);
+    if (threadIdx.x < 64) Ls[threadIdx.x] = lse_b[qt * 64 + threadIdx.x] * kLog2e;
+    else if (threadIdx.x < 128) Ds[threadIdx.x - 64] = del_b[qt * 64 + threadIdx.x - 64];
+    __syncthreads();
+    if (qt * 64 + 63 < k0) continue;  // every query of the tile precedes this wave's keys
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        s[mt] = MFMA(lds_frag(Qs + (mt * 32 + c) * LD + ks * 16 + g * 8), kf[ks], s[mt]);
+        dp[mt] = MFMA(lds_frag(Gs + (mt * 32 + c) * LD + ks * 16 + g * 8), vf[ks], dp[mt]);
+      }
+    const bool diag = qt * 64 < k0 + 31;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int ql = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);  // query row inside the tile
+        float p = exp2f(s[mt][r] * sc - Ls[ql]);
+        if (diag && qt * 64 + ql < kv) p = 0.f;
+        dp[mt][r] = p * (dp[mt][r] - Ds[ql]) * scale;  // dS
+        s[mt][r] = p;
+      }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pf = pack8(s[mt], 8 * t), df = pack8(dp[mt], 8 * t);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          dv[i] = MFMA(lds_frag_tr(Gs, LD, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), pf, dv[i]);
+          dk[i] = MFMA(lds_frag_tr(Qs, LD, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), df, dk[i]);
+        }
+      }
+  }
+  uint16_t *op = dqkv + ((int64_t)b * N + kv) * ld + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 wk = {pack2(dk[i][4 * j], dk[i][4 * j + 1]), pack2(dk[i][4 * j + 2], dk[i][4 * j + 3])};
+      u32x2 wv = {pack2(dv[i][4 * j], dv[i][4 * j + 1]), pack2(dv[i][4 * j + 2], dv[i][4 * j + 3])};
+      *reinterpret_cast<u32x2 *>(op + HD + i * 32 + 8 * j + 4 * g) = wk;
+      *reinterpret_cast<u32x2 *>(op + 2 * HD + i * 32 + 8 * j + 4 * g) = wv;
+    }
+}
+
+bool shape_ok(const void *a, const void *b, int N, int Hs, int dh) {
+  (void)Hs;
+  return (dh == 64 || dh == 128) && N % 128 == 0 && (reinterpret_cast<uintptr_t>(a) % 16) == 0 && (reinterpret_cast<uintptr_t>(b) % 16) == 0;
+}
+
+}  // namespace
+
+twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh, bool *done) {
+  static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
   *done = false;
+  if (off || !shape_ok(qkv, o, N, Hs, dh)) return TWIST_OK;
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
+  const uint16_t *x = static_cast<const uint16_t *>(qkv);
+  if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), lse, N, Hs, scale);
+  else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), lse, N, Hs, scale);
+  TW_HIP(ctx, hipGetLastError());
+  *done = true;
   return TWIST_OK;
 }
-twist_status twist_attention_bwd_mfma(twist_ctx *, const void *, const void *, const void *, const float *, float *, void *, int, int, int,
-                                      int, bool *done) {
+
+twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const void *o, const void *dout, const float *lse, float *delta, void *dqkv,
+                                      int B, int N, int Hs, int dh, bool *done) {
+  static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
+  (void)o;
   *done = false;
+  if (off || !shape_ok(qkv, dout, N, Hs, dh) || (reinterpret_cast<uintptr_t>(dqkv) % 16)) return TWIST_OK;
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
+  const uint16_t *x = static_cast<const uint16_t *>(qkv), *gout = static_cast<const uint16_t *>(dout);
+  uint16_t *dx = static_cast<uint16_t *>(dqkv);
+  if (dh == 128) {
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+  } else {
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+  }
+  TW_HIP(ctx, hipGetLastError());
+  *done = true;
   return TWIST_OK;
 }
