@@ -1,7 +1,7 @@
 // Dense projections of the subnet: C = epilogue(op(A) op(B)) with fp32 accumulation.
-//  - bf16 operands: MFMA kernel (v_mfma_f32_32x32x16_bf16), 128x128x32 workgroup tile, 4 waves of 64x64,
-//    operands staged through LDS as [row][k] so that each lane reads its 8 consecutive k values in one
-//    16-byte LDS load; operands whose memory layout has k as the slow axis are transposed while staging.
+//  - bf16 operands: MFMA kernel (v_mfma_f32_32x32x16_bf16), 256x256x32 or 128x128x32 workgroup tiles,
+//    operands staged through LDS in their memory orientation; operands whose contraction index is the slow
+//    axis in memory are read back with the transposing LDS load.
 //  - anything else (fp32 models, unaligned shapes): a plain tiled FMA kernel with arbitrary strides.
 #include "nn.h"
 
@@ -78,26 +78,36 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(int M, int N, int K, co
 }
 
 // ------------------------------------------------------------------------------------------- MFMA kernel
-constexpr int BM = 128, BN = 128, BK = 32, LDS_LD = BK + 8;  // padded row: 80 bytes, conflict-free 16-byte reads
-constexpr int kChunks = BM * BK / 8 / 256;                  // 16-byte chunks each thread stages per tile
-constexpr int kKC = BK / 8;                                 // chunks along k per row
+// Workgroup tile BM x BN x 32, WM x WN waves, each wave (BM/WM) x (BN/WN) in 32x32 MFMA tiles.
+// An operand tile lives in LDS in the orientation of its memory:
+//   k contiguous in memory ("KMAJOR"):  LDS [rows][32 + 8]; a lane's 8 k values are one 16-byte LDS read;
+//   rows contiguous in memory:          LDS [32][rows + 16]; a lane's 8 k values are two transposing reads
+//                                       (ds_read_tr16_b64: 4 consecutive k rows of one column each).
+// Both paddings make the reads bank-conflict free.  Tiles are double-buffered: the next tile's global loads
+// are issued before the MFMAs of the current one and written to the other buffer after them, one barrier per
+// k-iteration.  Workgroups are renumbered so that each of the 8 XCDs (own L2) works on a contiguous range
+// of tiles.
+constexpr int BK = 32;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// Stage a [128 rows][64 k] operand tile into LDS (row-major, k contiguous).
-//  KMAJOR = 1: memory is [row][k]  (k contiguous): 16-byte copies.
-//  KMAJOR = 0: memory is [k][row]  (row contiguous): 16-byte loads, transposed 2-byte LDS writes.
-template <int KMAJOR>
+template <int ROWS, int KMAJOR, int NT>
 struct TileLoader {
-  u32x4 reg[kChunks];
+  static constexpr int LD = KMAJOR ? BK + 8 : ROWS + 16;
+  static constexpr int ELEMS = KMAJOR ? ROWS * LD : BK * LD;
+  static constexpr int CHUNKS = ROWS * BK / 8 / NT;  // 16-byte chunks per thread
+  static constexpr int CPR = KMAJOR ? BK / 8 : ROWS / 8;  // chunks per stored row
+  u32x4 reg[CHUNKS];
   __device__ __forceinline__ void load(const uint16_t *src, int64_t ld, int row0, int k0, int rows, int K) {
 #pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int c = threadIdx.x + 256 * i;
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = threadIdx.x + NT * i;
       reg[i] = u32x4{0, 0, 0, 0};
       if (KMAJOR) {
-        const int r = c / kKC, kc = (c % kKC) * 8;
+        const int r = c / CPR, kc = (c % CPR) * 8;
         if (row0 + r < rows && k0 + kc < K) reg[i] = *reinterpret_cast<const u32x4 *>(src + (int64_t)(row0 + r) * ld + k0 + kc);
       } else {
-        const int k = c >> 4, rc = (c & 15) * 8;
+        const int k = c / CPR, rc = (c % CPR) * 8;
         if (k0 + k < K && row0 + rc < rows) {
           const uint16_t *p = src + (int64_t)(k0 + k) * ld + row0 + rc;
           if (row0 + rc + 8 <= rows) reg[i] = *reinterpret_cast<const u32x4 *>(p);
@@ -114,46 +124,59 @@ struct TileLoader {
   }
   __device__ __forceinline__ void store(uint16_t *lds) const {
 #pragma unroll
-    for (int i = 0; i < kChunks; ++i) {
-      const int c = threadIdx.x + 256 * i;
-      if (KMAJOR) {
-        const int r = c / kKC, kc = (c % kKC) * 8;
-        *reinterpret_cast<u32x4 *>(lds + r * LDS_LD + kc) = reg[i];
-      } else {
-        const int k = c >> 4, rc = (c & 15) * 8;
-        const uint32_t w[4] = {reg[i].x, reg[i].y, reg[i].z, reg[i].w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          lds[(rc + 2 * j) * LDS_LD + k] = (uint16_t)(w[j] & 0xffff);
-          lds[(rc + 2 * j + 1) * LDS_LD + k] = (uint16_t)(w[j] >> 16);
-        }
-      }
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = threadIdx.x + NT * i;
+      const int r = c / CPR, kc = (c % CPR) * 8;  // (row, k chunk) or (k row, row chunk): same arithmetic
+      *reinterpret_cast<u32x4 *>(lds + r * LD + kc) = reg[i];
     }
+  }
+  // fragment for the 32 rows starting at row0 of the tile, k-step ks (16 wide)
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t *lds, int row0, int ks) {
+    const int lane = threadIdx.x & 63;
+    if (KMAJOR) return *reinterpret_cast<const bf16x8 *>(lds + (row0 + (lane & 31)) * LD + ks * 16 + (lane >> 5) * 8);
+    const int s = lane & 15;
+    const uint16_t *p = lds + (ks * 16 + (lane >> 5) * 8 + (s >> 2)) * LD + row0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * LD));
+    s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    return __builtin_bit_cast(bf16x8, v);
   }
 };
 
-// A operand: rows = M index; B operand: rows = N index.  AK / BK_ say whether k is contiguous in memory.
-template <int AK, int BK_>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, Ep ep,
-                                                        int tiles_n) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDS_LD];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDS_LD];
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+// A operand: rows = M index; B operand: rows = N index.  AKM / BKM say whether k is contiguous in memory.
+template <int AKM, int BKM, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, int K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                                                                Ep ep, int tiles_m, int tiles_n) {
+  constexpr int NT = WM * WN * 64, TM = BM / WM / 32, TN = BN / WN / 32;
+  using LA = TileLoader<BM, AKM, NT>;
+  using LB = TileLoader<BN, BKM, NT>;
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][LA::ELEMS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][LB::ELEMS];
+  // XCD-aware renumbering: hardware deals workgroup ids round-robin over 8 XCDs
+  const int nb = tiles_m * tiles_n;
+  int bid = blockIdx.x;
+  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
+  // walk the tiles in column-panels of 8 tile rows so that concurrently running workgroups share operands
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int grp = bid / per_group, first_m = grp * GROUP;
+  const int gsize = min(GROUP, tiles_m - first_m);
+  const int tile_m = first_m + (bid % per_group) % gsize, tile_n = (bid % per_group) / gsize;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const int lr = lane & 31, lk = (lane >> 5) * 8;
+  const int wm = (wave / WN) * (BM / WM), wn = (wave % WN) * (BN / WN);
 
-  f32x16 acc[2][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  TileLoader<AK> la;
-  TileLoader<BK_> lb;
+  LA la;
+  LB lb;
   la.load(A, lda, m0, 0, M, K);
   lb.load(B, ldb, n0, 0, N, K);
   la.store(As[0]);
@@ -168,16 +191,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[2], bfr[2];
+      bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8 *>(As[cur] + (wm + i * 32 + lr) * LDS_LD + ks * 16 + lk);
-        bfr[i] = *reinterpret_cast<const bf16x8 *>(Bs[cur] + (wn + i * 32 + lr) * LDS_LD + ks * 16 + lk);
-      }
+      for (int i = 0; i < TM; ++i) af[i] = LA::frag(As[cur], wm + i * 32, ks);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < TN; ++j) bfr[j] = LB::frag(Bs[cur], wn + j * 32, ks);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
       la.store(As[cur ^ 1]);
@@ -187,16 +209,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int M, int N, int K, con
   }
   // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn + j * 32 + lr;
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (m < M && n < N) store_out<1>(ep, m, n, acc[i][j][r]);
       }
     }
+}
+
+template <int AKM, int BKM>
+void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
+  // 256x256 tiles (8 waves of 64x128) when they fill the chip, else 128x128 (4 waves of 64x64)
+  const int big = ((M + 255) / 256) * ((N + 255) / 256);
+  const char *force = getenv("TWIST_GEMM_TILE");  // test knob: "256" or "128" pins the tile size
+  const bool use_big = force ? atoi(force) == 256 : big >= 200;
+  if (use_big) {
+    const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+    hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 256, 256, 4, 2>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+  } else {
+    const int tm = (M + 127) / 128, tn = (N + 127) / 128;
+    hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 128, 128, 2, 2>), dim3(tm * tn), dim3(256), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+  }
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -227,14 +264,11 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   const bool k_ok = lay == GEMM_TN || K % 8 == 0 || (lay == GEMM_NN && lda >= (K + 7) / 8 * 8);
   const bool vec_ok = bf16 && !no_mfma && aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && k_ok;
   if (vec_ok) {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const size_t smem = 0;
     const uint16_t *a = static_cast<const uint16_t *>(A), *b = static_cast<const uint16_t *>(B);
-    dim3 grid(tiles_m * tiles_n), block(256);
     switch (lay) {
-      case GEMM_NT: hipLaunchKernelGGL((gemm_mfma_kernel<1, 1>), grid, block, smem, ctx->stream, M, N, K, a, lda, b, ldb, ep, tiles_n); break;
-      case GEMM_NN: hipLaunchKernelGGL((gemm_mfma_kernel<1, 0>), grid, block, smem, ctx->stream, M, N, K, a, lda, b, ldb, ep, tiles_n); break;
-      case GEMM_TN: hipLaunchKernelGGL((gemm_mfma_kernel<0, 0>), grid, block, smem, ctx->stream, M, N, K, a, lda, b, ldb, ep, tiles_n); break;
+      case GEMM_NT: launch_mfma<1, 1>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_NN: launch_mfma<1, 0>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_TN: launch_mfma<0, 0>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
     }
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
