@@ -186,6 +186,14 @@ TWIST_API twist_status twist_subnet_step(twist_ctx *ctx, twist_subnet *sub, cons
 TWIST_API twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, twist_subnet *const *subs, int32_t n_subs,
                              const twist_full_weights *inout);
 
+/* Kernel-level entry point for tests and benchmarks: one projection of the subnet forward/backward pass in
+ * isolation, C = alpha * op(A) op(B), fp32 accumulation, on the ctx's stream (Appendix A.1: Q_h = X W^Q_h etc.;
+ * the backward pass uses the two transposed forms).  layout 0: A [M,K], B [N,K] (y = x W^T); 1: A [M,K], B [K,N]
+ * (dx = dy W); 2: A stored [K,M], B stored [K,N] (dW = dy^T x).  All row-major device pointers of desc.dtype
+ * with row strides lda/ldb/ldc in elements; C is fp32 when out_f32 != 0, else desc.dtype. */
+TWIST_API twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, int64_t lda,
+                                      const void *B, int64_t ldb, void *C, int64_t ldc, int32_t out_f32, float alpha);
+
 /* Measurement aid for benchmarks (not part of the method): while enabled, every projection (GEMM) launch on
  * this ctx is bracketed by two HIP events on the ctx's stream.  twist_profile_gemm_read synchronises the
  * stream, returns the number of launches, their summed duration in milliseconds and their summed algorithmic

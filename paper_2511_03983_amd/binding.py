@@ -80,6 +80,7 @@ _SIGS = {
     "twist_subnet_fwd_bwd": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
+    "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
     "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
 }
@@ -162,6 +163,12 @@ class Context:
         arr = (_vp * len(subs))(*[s.h for s in subs])
         _check(lib.twist_aggregate(self.h, plan.h, arr, len(subs), C.byref(full.c)), self.h)
 
+
+    def twist_gemm_raw(self, layout: int, M: int, N: int, K: int, A: torch.Tensor, B: torch.Tensor, out: torch.Tensor, alpha: float = 1.0) -> None:
+        """out[M,N] = alpha * op(A) op(B); layouts as in include/twist.h; row strides taken from the tensors."""
+        _check(lib.twist_gemm_raw(self.h, layout, M, N, K, _vp(A.data_ptr()), A.stride(0), _vp(B.data_ptr()), B.stride(0),
+                                  _vp(out.data_ptr()), out.stride(0), int(out.dtype == torch.float32 and self.torch_dtype != torch.float32
+                                                                          or out.dtype == torch.float32), alpha), self.h)
 
     def twist_profile_gemm(self, enable: bool) -> None:
         _check(lib.twist_profile_gemm(self.h, int(enable)), self.h)

@@ -87,39 +87,54 @@ __global__ __launch_bounds__(256) void gemm_plain_kernel(int M, int N, int K, co
 // are issued before the MFMAs of the current one and written to the other buffer after them, one barrier per
 // k-iteration.  Workgroups are renumbered so that each of the 8 XCDs (own L2) works on a contiguous range
 // of tiles.
-constexpr int BK = 32;
+constexpr int BK = 64;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+constexpr uint32_t kOob = 0x80000000u;  // byte offset beyond every buffer: loads return 0, stores are dropped
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+// Global accesses go through buffer instructions whose hardware range check returns zeros (loads) or drops the
+// access (stores) beyond the end, so tile edges need no branches: an out-of-range row or k chunk just gets an
+// offset outside the buffer.
 template <int ROWS, int KMAJOR, int NT>
 struct TileLoader {
   static constexpr int LD = KMAJOR ? BK + 8 : ROWS + 16;
   static constexpr int ELEMS = KMAJOR ? ROWS * LD : BK * LD;
-  static constexpr int CHUNKS = ROWS * BK / 8 / NT;  // 16-byte chunks per thread
+  static constexpr int CHUNKS = ROWS * BK / 8 / NT;       // 16-byte chunks per thread
   static constexpr int CPR = KMAJOR ? BK / 8 : ROWS / 8;  // chunks per stored row
   u32x4 reg[CHUNKS];
-  __device__ __forceinline__ void load(const uint16_t *src, int64_t ld, int row0, int k0, int rows, int K) {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t off[CHUNKS];  // byte offset of each chunk at k0 = 0 (kOob if its row is outside the operand)
+  int kk[CHUNKS];        // k of the chunk inside a tile
+  uint32_t kstep;        // bytes to advance per k-tile
+  // base = first row of this workgroup's panel (KMAJOR) or first column (otherwise)
+  __device__ __forceinline__ void init(const uint16_t *base, int64_t ld, int rows_left, int K) {
+    const int64_t span = KMAJOR ? ((int64_t)(min(rows_left, ROWS) - 1) * ld + K) : ((int64_t)(K - 1) * ld + min(rows_left, (int)ld));
+    rsrc = make_rsrc(base, (uint32_t)(span * 2));
+    kstep = KMAJOR ? BK * 2 : (uint32_t)(BK * ld * 2);
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) {
       const int c = threadIdx.x + NT * i;
-      reg[i] = u32x4{0, 0, 0, 0};
       if (KMAJOR) {
         const int r = c / CPR, kc = (c % CPR) * 8;
-        if (row0 + r < rows && k0 + kc < K) reg[i] = *reinterpret_cast<const u32x4 *>(src + (int64_t)(row0 + r) * ld + k0 + kc);
+        kk[i] = kc;
+        off[i] = r < rows_left ? (uint32_t)((r * ld + kc) * 2) : kOob;
       } else {
         const int k = c / CPR, rc = (c % CPR) * 8;
-        if (k0 + k < K && row0 + rc < rows) {
-          const uint16_t *p = src + (int64_t)(k0 + k) * ld + row0 + rc;
-          if (row0 + rc + 8 <= rows) reg[i] = *reinterpret_cast<const u32x4 *>(p);
-          else {  // ragged edge: element-wise
-            uint16_t t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            for (int j = 0; j < 8; ++j)
-              if (row0 + rc + j < rows) t[j] = p[j];
-            reg[i] = u32x4{(uint32_t)t[0] | ((uint32_t)t[1] << 16), (uint32_t)t[2] | ((uint32_t)t[3] << 16),
-                           (uint32_t)t[4] | ((uint32_t)t[5] << 16), (uint32_t)t[6] | ((uint32_t)t[7] << 16)};
-          }
-        }
+        kk[i] = k;
+        off[i] = rc < rows_left ? (uint32_t)((k * ld + rc) * 2) : kOob;
       }
+    }
+  }
+  __device__ __forceinline__ void load(int kt, int K) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const uint32_t o = (kt * BK + kk[i] < K) ? off[i] + kt * kstep : kOob;
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, 0);
     }
   }
   __device__ __forceinline__ void store(uint16_t *lds) const {
@@ -148,7 +163,7 @@ struct TileLoader {
 template <int AKM, int BKM, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, int K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
                                                                 Ep ep, int tiles_m, int tiles_n) {
-  constexpr int NT = WM * WN * 64, TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int NT = WM * WN * 64, TM = BM / WM / 32, TN = BN / WN / 32, KS = BK / 16;
   using LA = TileLoader<BM, AKM, NT>;
   using LB = TileLoader<BN, BKM, NT>;
   __shared__ __attribute__((aligned(16))) uint16_t As[2][LA::ELEMS];
@@ -177,8 +192,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
 
   LA la;
   LB lb;
-  la.load(A, lda, m0, 0, M, K);
-  lb.load(B, ldb, n0, 0, N, K);
+  la.init(AKM ? A + (int64_t)m0 * lda : A + m0, lda, M - m0, K);
+  lb.init(BKM ? B + (int64_t)n0 * ldb : B + n0, ldb, N - n0, K);
+  la.load(0, K);
+  lb.load(0, K);
   la.store(As[0]);
   lb.store(Bs[0]);
   __syncthreads();
@@ -186,20 +203,27 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
-      la.load(A, lda, m0, (kt + 1) * BK, M, K);
-      lb.load(B, ldb, n0, (kt + 1) * BK, N, K);
+      la.load(kt + 1, K);
+      lb.load(kt + 1, K);
     }
+    // fragments of k-step ks+1 are fetched while the MFMAs of k-step ks run
+    bf16x8 af[2][TM], bfr[2][TN];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[TM], bfr[TN];
+    for (int i = 0; i < TM; ++i) af[0][i] = LA::frag(As[cur], wm + i * 32, 0);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = LA::frag(As[cur], wm + i * 32, ks);
+    for (int j = 0; j < TN; ++j) bfr[0][j] = LB::frag(Bs[cur], wn + j * 32, 0);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = LB::frag(Bs[cur], wn + j * 32, ks);
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[(ks + 1) & 1][i] = LA::frag(As[cur], wm + i * 32, ks + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[(ks + 1) & 1][j] = LB::frag(Bs[cur], wn + j * 32, ks + 1);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
       la.store(As[cur ^ 1]);
@@ -207,18 +231,32 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
     }
     __syncthreads();
   }
-  // accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
+
+  // Epilogue.  Accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4.
+  const int esz = ep.out_f32 ? 4 : 2;
+  const int rows_left = M - m0;
+  char *cbase = static_cast<char *>(ep.out) + ((int64_t)m0 * ep.ldc) * esz;
+  const __amdgpu_buffer_rsrc_t crs = make_rsrc(cbase, (uint32_t)(((int64_t)(min(rows_left, BM) - 1) * ep.ldc + N) * esz));
+  const float *rbase = ep.residual ? ep.residual + (int64_t)m0 * ep.ldc : nullptr;
+  const __amdgpu_buffer_rsrc_t rrs = make_rsrc(rbase, rbase ? (uint32_t)(((int64_t)(min(rows_left, BM) - 1) * ep.ldc + N) * 4) : 0u);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn + j * 32 + (lane & 31);
+    const bool n_ok = n < N;
+    float bias = 0.f;
+    if (ep.bias && n_ok) bias = bf2f(static_cast<const uint16_t *>(ep.bias)[n]);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn + j * 32 + (lane & 31);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < M && n < N) store_out<1>(ep, m, n, acc[i][j][r]);
+        const int ml = wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const uint32_t eoff = (n_ok && ml < rows_left) ? (uint32_t)(ml * ep.ldc + n) : kOob;
+        float v = (acc[i][j][r] + bias) * ep.alpha;
+        if (ep.residual) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rrs, eoff == kOob ? kOob : eoff * 4, 0, 0));
+        if (ep.out_f32) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), crs, eoff == kOob ? kOob : eoff * 4, 0, 0);
+        else __builtin_amdgcn_raw_buffer_store_b16(f2bf(v), crs, eoff == kOob ? kOob : eoff * 2, 0, 0);
       }
-    }
+  }
 }
 
 template <int AKM, int BKM>
@@ -262,7 +300,10 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   // 16-byte chunks along k must not straddle the end of an operand row.  For y = x W with a ragged K the
   // caller pads x's rows (lda >= K rounded up to 8) with zeros; W's rows beyond K are never touched.
   const bool k_ok = lay == GEMM_TN || K % 8 == 0 || (lay == GEMM_NN && lda >= (K + 7) / 8 * 8);
-  const bool vec_ok = bf16 && !no_mfma && aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && k_ok;
+  // buffer offsets are 32-bit: a row panel (256 rows) or a k-panel (K rows) of each operand and of C must stay below 2 GiB
+  const int64_t a_span = (lay == GEMM_TN ? (int64_t)K : 256) * lda * 2, b_span = (lay == GEMM_NT ? 256 : (int64_t)K) * ldb * 2;
+  const bool span_ok = a_span < (1ll << 31) && b_span < (1ll << 31) && 256 * ldc * 4 < (1ll << 31);
+  const bool vec_ok = bf16 && !no_mfma && aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && k_ok && span_ok;
   if (vec_ok) {
     const uint16_t *a = static_cast<const uint16_t *>(A), *b = static_cast<const uint16_t *>(B);
     switch (lay) {
@@ -284,6 +325,19 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   else hipLaunchKernelGGL(gemm_plain_kernel<0>, grid, block, 0, ctx->stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
+}
+
+extern "C" twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, int64_t lda, const void *B,
+                                       int64_t ldb, void *C, int64_t ldc, int32_t out_f32, float alpha) {
+  if (!ctx || !A || !B || !C) TW_FAIL(ctx, TWIST_EINVAL, "twist_gemm_raw: null argument");
+  if (layout < 0 || layout > 2 || M < 0 || N < 0 || K < 0) TW_FAIL(ctx, TWIST_EINVAL, "twist_gemm_raw: bad layout or size");
+  const int64_t need_a = layout == GEMM_TN ? M : K, need_b = layout == GEMM_NT ? K : N;
+  if (lda < need_a || ldb < need_b || ldc < N) TW_FAIL(ctx, TWIST_ESHAPE, "twist_gemm_raw: a row stride is smaller than the row it strides");
+  GemmEpilogue e;
+  e.alpha = alpha;
+  e.out = C;
+  e.out_f32 = out_f32;
+  return twist_gemm(ctx, ctx->d.dtype == TWIST_BF16, (GemmLayout)layout, M, N, K, A, lda, B, ldb, ldc, e);
 }
 
 extern "C" twist_status twist_profile_gemm(twist_ctx *ctx, int32_t enable) {
