@@ -194,17 +194,27 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
   LB lb;
   la.init(AKM ? A + (int64_t)m0 * lda : A + m0, lda, M - m0, K);
   lb.init(BKM ? B + (int64_t)n0 * ldb : B + n0, ldb, N - n0, K);
+  // Pipeline: tile kt+2 travels from global memory to registers and tile kt+1 from registers to LDS while
+  // tile kt is multiplied; one barrier per k-iteration.
   la.load(0, K);
   lb.load(0, K);
   la.store(As[0]);
   lb.store(Bs[0]);
-  __syncthreads();
   const int nk = (K + BK - 1) / BK;
+  if (nk > 1) {
+    la.load(1, K);
+    lb.load(1, K);
+  }
+  __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
-      la.load(kt + 1, K);
-      lb.load(kt + 1, K);
+      la.store(As[cur ^ 1]);
+      lb.store(Bs[cur ^ 1]);
+    }
+    if (kt + 2 < nk) {
+      la.load(kt + 2, K);
+      lb.load(kt + 2, K);
     }
     // fragments of k-step ks+1 are fetched while the MFMAs of k-step ks run
     bf16x8 af[2][TM], bfr[2][TN];
@@ -224,10 +234,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      la.store(As[cur ^ 1]);
-      lb.store(Bs[cur ^ 1]);
     }
     __syncthreads();
   }
