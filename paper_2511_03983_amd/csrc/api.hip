@@ -361,7 +361,11 @@ bool make_job(const twist_ctx *ctx, const twist_plan *plan, int l, int t, const 
   }
   jb.vec = ((int64_t)jb.Q * es) % 16 == 0 && (reinterpret_cast<uintptr_t>(full_ptr) % 16) == 0;
   const int64_t width = (int64_t)(for_aggregate ? jb.n_full : jb.n_sub) * (jb.vec ? jb.Q / VN : jb.Q);
-  if (jb.vec) {
+  if (jb.vec && for_aggregate) {
+    // the pull keeps up to 8 subnets' vectors per output vector in registers: fewer vectors per thread
+    jb.tile_u = jb.rows == 1 ? (width >= 1024 ? 4 : (width >= 512 ? 2 : 1)) : (width >= 512 ? 2 : 1);
+    jb.tile_rows = jb.tile_u == 4 ? 1 : (jb.tile_u == 2 ? (jb.rows > 1 ? 2 : 1) : 4);
+  } else if (jb.vec) {
     jb.tile_u = width >= 1024 ? 4 : (width >= 512 ? 2 : 1);
     jb.tile_rows = 4 / jb.tile_u;
   } else {

@@ -78,46 +78,52 @@ __device__ __forceinline__ void gather_vec(const MoveJob &jb, char *dst_base, in
   }
 }
 
+// Element path: a thread owns two ADJACENT destination elements of the tile (one packed store when the
+// element is 2 bytes), keeps their source columns in registers and walks the rows of the tile, eight at a
+// time so that sixteen independent loads are in flight.  Consecutive lanes read a short ascending span of the
+// source row and write consecutive bytes.
 template <int ES>
 __device__ __forceinline__ void gather_elem(const MoveJob &jb, char *dst_base, int lb) {
   using E = typename VecOf<ES>::elem;
-  constexpr int TU = 2;
+  constexpr int RU = 8;
   const int64_t Ws = (int64_t)jb.n_sub * jb.Q, Wf = (int64_t)jb.n_full * jb.Q;
   const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
   const E *src = reinterpret_cast<const E *>(jb.full);
   E *dst = reinterpret_cast<E *>(dst_base + jb.sub_off * ES);
-  int64_t dv[TU], sv[TU];
+  const int64_t v0 = (int64_t)ct * (kThreads * 2) + 2 * threadIdx.x;
+  if (v0 >= Ws) return;
+  const bool two = v0 + 1 < Ws;
+  int64_t sv[2];
 #pragma unroll
-  for (int u = 0; u < TU; ++u) {
-    int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
-    dv[u] = v < Ws ? v : -1;
-    sv[u] = 0;
-    if (v < Ws) {
-      int k = (int)(v / jb.Q);
-      int j = (int)(v - (int64_t)k * jb.Q);
-      sv[u] = jb.table ? (int64_t)jb.table[k] * jb.Q + j : v;
-    }
+  for (int u = 0; u < 2; ++u) {
+    const int64_t v = two || u == 0 ? v0 + u : v0;
+    const int k = (int)(v / jb.Q);
+    const int j = (int)(v - (int64_t)k * jb.Q);
+    sv[u] = jb.table ? (int64_t)jb.table[k] * jb.Q + j : v;
   }
   const int r0 = rt * jb.tile_rows;
   const int r1 = min(r0 + jb.tile_rows, jb.rows);
+  const bool packed = ES == 2 && two && (Ws & 1) == 0 && ((reinterpret_cast<uintptr_t>(dst) & 3) == 0);
   int row = r0;
-  for (; row + 4 <= r1; row += 4) {
-    E val[4][TU];
+  for (; row + RU <= r1; row += RU) {
+    E val[RU][2];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < RU; ++r) {
+      val[r][0] = src[(row + r) * Wf + sv[0]];
+      val[r][1] = src[(row + r) * Wf + sv[1]];
+    }
 #pragma unroll
-      for (int u = 0; u < TU; ++u)
-        if (dv[u] >= 0) val[r][u] = src[(row + r) * Wf + sv[u]];
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-      for (int u = 0; u < TU; ++u)
-        if (dv[u] >= 0) dst[(row + r) * Ws + dv[u]] = val[r][u];
+    for (int r = 0; r < RU; ++r) {
+      E *d = dst + (row + r) * Ws + v0;
+      if (packed) *reinterpret_cast<uint32_t *>(d) = (uint32_t)val[r][0] | ((uint32_t)val[r][1] << 16);
+      else { d[0] = val[r][0]; if (two) d[1] = val[r][1]; }
+    }
   }
-  for (; row < r1; ++row)
-#pragma unroll
-    for (int u = 0; u < TU; ++u)
-      if (dv[u] >= 0) dst[row * Ws + dv[u]] = src[row * Wf + sv[u]];
+  for (; row < r1; ++row) {
+    E *d = dst + row * Ws + v0;
+    d[0] = src[row * Wf + sv[0]];
+    if (two) d[1] = src[row * Wf + sv[1]];
+  }
 }
 
 template <int ES>
@@ -187,6 +193,9 @@ template <> __device__ __forceinline__ uint32_t f32_to_elem<4>(float f) { return
 
 constexpr int kChunk = 8;  // subnets whose loads are issued together
 
+// Vector path of the pull.  Three phases so that the two dependent memory round trips (inverse table, then
+// data) are each paid once per thread, not once per vector: all table lookups, then all data loads, then the
+// sums and the stores.  With more than kChunk subnets the phases repeat per chunk of subnets.
 template <int ES, int TR, int TU>
 __device__ __forceinline__ void pull_vec(const MoveLaunch &ml, const MoveJob &jb, int lb) {
   using V = typename VecOf<ES>::vec;
@@ -195,96 +204,150 @@ __device__ __forceinline__ void pull_vec(const MoveLaunch &ml, const MoveJob &jb
   const int64_t Ws = (int64_t)jb.n_sub * qv, Wf = (int64_t)jb.n_full * qv;
   const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
   V *full = reinterpret_cast<V *>(const_cast<void *>(jb.full));
+  int64_t v[TU];
+  int unit[TU], j[TU];
 #pragma unroll
   for (int u = 0; u < TU; ++u) {
-    const int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
-    if (v >= Wf) continue;
-    const int unit = (int)(v / qv);
-    const int j = (int)(v - (int64_t)unit * qv);
-    Acc<ES> acc[TR];
-    int cnt = 0;
-    for (int c0 = 0; c0 < ml.n_subs; c0 += kChunk) {
-      int p[kChunk];
+    v[u] = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
+    const int64_t vc = v[u] < Wf ? v[u] : 0;
+    unit[u] = (int)(vc / qv);
+    j[u] = (int)(vc - (int64_t)unit[u] * qv);
+  }
+  Acc<ES> acc[TU][TR];
+  int cnt[TU];
+#pragma unroll
+  for (int u = 0; u < TU; ++u) cnt[u] = 0;
+  for (int c0 = 0; c0 < ml.n_subs; c0 += kChunk) {
+    int p[TU][kChunk];
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
 #pragma unroll
       for (int i = 0; i < kChunk; ++i) {
-        p[i] = -1;
-        if (c0 + i < ml.n_subs) p[i] = jb.table ? jb.table[(int64_t)ml.sub_row[c0 + i] * jb.n_full + unit] : 0;
+        p[u][i] = -1;
+        if (c0 + i < ml.n_subs && v[u] < Wf) p[u][i] = jb.table ? jb.table[(int64_t)ml.sub_row[c0 + i] * jb.n_full + unit[u]] : 0;
       }
-      V val[kChunk][TR];
+    V val[TU][kChunk][TR];
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
 #pragma unroll
       for (int i = 0; i < kChunk; ++i)
-        if (p[i] >= 0) {
-          const V *sp = reinterpret_cast<const V *>(ml.sub_base[c0 + i] + jb.sub_off * ES) + (int64_t)p[i] * qv + j;
+        if (p[u][i] >= 0) {
+          const V *sp = reinterpret_cast<const V *>(ml.sub_base[c0 + i] + jb.sub_off * ES) + (int64_t)p[u][i] * qv + j[u];
 #pragma unroll
           for (int r = 0; r < TR; ++r) {
             const int row = rt * TR + r;
-            if (row < jb.rows) val[i][r] = __builtin_nontemporal_load(&sp[row * Ws]);
+            if (row < jb.rows) val[u][i][r] = __builtin_nontemporal_load(&sp[row * Ws]);
           }
         }
+#pragma unroll
+    for (int u = 0; u < TU; ++u)
 #pragma unroll
       for (int i = 0; i < kChunk; ++i)
-        if (p[i] >= 0) {
+        if (p[u][i] >= 0) {
 #pragma unroll
           for (int r = 0; r < TR; ++r) {
-            if (cnt == 0) acc[r].set(val[i][r]); else acc[r].add(val[i][r]);
+            if (cnt[u] == 0) acc[u][r].set(val[u][i][r]); else acc[u][r].add(val[u][i][r]);
           }
-          ++cnt;
+          ++cnt[u];
         }
-    }
-    if (cnt > 0) {
+  }
+#pragma unroll
+  for (int u = 0; u < TU; ++u)
+    if (cnt[u] > 0) {
 #pragma unroll
       for (int r = 0; r < TR; ++r) {
         const int row = rt * TR + r;
-        if (row < jb.rows) __builtin_nontemporal_store(acc[r].mean(cnt), &full[row * Wf + v]);
+        if (row < jb.rows) __builtin_nontemporal_store(acc[u][r].mean(cnt[u]), &full[row * Wf + v[u]]);
       }
     }
-  }
 }
 
+// Element path of the pull: a thread owns two adjacent central elements.  Their positions in every subnet are
+// looked up once and reused for all rows of the tile.  Loads are unconditional (a subnet that does not hold the
+// unit is read at position 0 and masked out), so no lane diverges and 4 rows x 8 subnets x 2 elements of loads
+// are in flight; sums are formed in subnet order, starting from the first owner's value itself so that a
+// single-owner element is copied bit for bit.
 template <int ES>
 __device__ __forceinline__ void pull_elem(const MoveLaunch &ml, const MoveJob &jb, int lb) {
   using E = typename VecOf<ES>::elem;
-  constexpr int TU = 2;
+  constexpr int RU = 2;
   const int64_t Ws = (int64_t)jb.n_sub * jb.Q, Wf = (int64_t)jb.n_full * jb.Q;
   const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
   E *full = reinterpret_cast<E *>(const_cast<void *>(jb.full));
   const int r0 = rt * jb.tile_rows;
   const int r1 = min(r0 + jb.tile_rows, jb.rows);
+  const int64_t v0 = (int64_t)ct * (kThreads * 2) + 2 * threadIdx.x;
+  if (v0 >= Wf) return;
+  const bool two = v0 + 1 < Wf;
+  if (ml.n_subs <= kChunk) {
+    int64_t pos[kChunk][2];
+    bool ok[kChunk][2];
+    int have[2] = {0, 0};
 #pragma unroll
-  for (int u = 0; u < TU; ++u) {
-    const int64_t v = (int64_t)ct * (kThreads * TU) + u * kThreads + threadIdx.x;
-    if (v >= Wf) continue;
-    const int unit = (int)(v / jb.Q);
-    const int j = (int)(v - (int64_t)unit * jb.Q);
-    if (ml.n_subs <= kChunk) {
-      // common case: the positions of this element in all subnets fit in registers and are reused
-      // for every row of the tile
-      int64_t pos[kChunk];
-      int have = 0;
+    for (int u = 0; u < 2; ++u) {
+      const int64_t v = (two || u == 0) ? v0 + u : v0;
+      const int unit = (int)(v / jb.Q);
+      const int j = (int)(v - (int64_t)unit * jb.Q);
 #pragma unroll
       for (int i = 0; i < kChunk; ++i) {
-        pos[i] = -1;
-        if (i < ml.n_subs) {
-          int p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
-          if (p >= 0) { pos[i] = (int64_t)p * jb.Q + j; ++have; }
+        int p = -1;
+        if (i < ml.n_subs) p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+        ok[i][u] = p >= 0 && (u == 0 || two);
+        pos[i][u] = ok[i][u] ? (int64_t)p * jb.Q + j : 0;
+        have[u] += ok[i][u] ? 1 : 0;
+      }
+    }
+    if (have[0] == 0 && have[1] == 0) return;  // no owner: the central values stay
+    const float c0 = (float)max(have[0], 1), c1 = (float)max(have[1], 1);
+    const bool packed = ES == 2 && have[0] > 0 && have[1] > 0 && (Wf & 1) == 0 && ((reinterpret_cast<uintptr_t>(full) & 3) == 0);
+    auto reduce_store = [&](const E (&val)[kChunk][2], int row) {
+      float acc[2] = {0.f, 0.f};
+      bool seen[2] = {false, false};
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const float x = elem_to_f32<ES>(val[i][u]);
+          acc[u] = ok[i][u] ? (seen[u] ? acc[u] + x : x) : acc[u];
+          seen[u] = seen[u] || ok[i][u];
         }
-      }
-      if (have == 0) continue;  // no owner: the central value stays
-      const float c = (float)have;
-      for (int row = r0; row < r1; ++row) {
-        E val[kChunk];
+      E *d = full + row * Wf + v0;
+      const E o0 = f32_to_elem<ES>(acc[0] / c0), o1 = f32_to_elem<ES>(acc[1] / c1);
+      if (packed) *reinterpret_cast<uint32_t *>(d) = (uint32_t)o0 | ((uint32_t)o1 << 16);
+      else { if (have[0]) d[0] = o0; if (have[1]) d[1] = o1; }
+    };
+    int row = r0;
+    for (; row + RU <= r1; row += RU) {
+      E val[RU][kChunk][2];
+#pragma unroll
+      for (int r = 0; r < RU; ++r)
 #pragma unroll
         for (int i = 0; i < kChunk; ++i)
-          if (pos[i] >= 0) val[i] = reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES)[row * Ws + pos[i]];
-        float acc = 0.f;
-        bool first = true;
+          if (i < ml.n_subs) {
+            const E *sp = reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES) + (row + r) * Ws;
+            val[r][i][0] = sp[pos[i][0]];
+            val[r][i][1] = sp[pos[i][1]];
+          }
 #pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-          if (pos[i] >= 0) { acc = first ? elem_to_f32<ES>(val[i]) : acc + elem_to_f32<ES>(val[i]); first = false; }
-        full[row * Wf + v] = f32_to_elem<ES>(acc / c);
-      }
-    } else {
-      // more subnets than one chunk: plain loop over all of them per row
+      for (int r = 0; r < RU; ++r) reduce_store(val[r], row + r);
+    }
+    for (; row < r1; ++row) {
+      E val[kChunk][2];
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i)
+        if (i < ml.n_subs) {
+          const E *sp = reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES) + row * Ws;
+          val[i][0] = sp[pos[i][0]];
+          val[i][1] = sp[pos[i][1]];
+        }
+      reduce_store(val, row);
+    }
+  } else {
+    // more subnets than one chunk: plain loop over all of them per row
+    for (int u = 0; u < (two ? 2 : 1); ++u) {
+      const int64_t v = v0 + u;
+      const int unit = (int)(v / jb.Q);
+      const int j = (int)(v - (int64_t)unit * jb.Q);
       for (int row = r0; row < r1; ++row) {
         float acc = 0.f;
         int cnt = 0;
@@ -309,6 +372,7 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const MoveLaunch ml
   const int lb = blockIdx.x - jb.blk_begin;
   if (jb.vec) {
     if (jb.tile_u == 4) pull_vec<ES, 1, 4>(ml, jb, lb);
+    else if (jb.tile_u == 2 && jb.tile_rows == 1) pull_vec<ES, 1, 2>(ml, jb, lb);
     else if (jb.tile_u == 2) pull_vec<ES, 2, 2>(ml, jb, lb);
     else pull_vec<ES, 4, 1>(ml, jb, lb);
   } else {
