@@ -198,7 +198,7 @@ def bench_movers(args, tw, si, torch):
 
 def cpu_baseline(si):
     """The CPU checker as it stands, timed on a bounded sample of the same workload: the Llama-1B-shaped
-    half-width subnet at full widths and vocabulary with 1 and 2 layers on 1 x 128 tokens; the per-layer
+    half-width subnet at full widths and vocabulary with 1 and 2 layers on 2 x 1024 tokens; the per-layer
     and the embedding/head costs are separated and extrapolated to the 22-layer model."""
     import numpy as np
     from oracle import model as omodel, move as omove
@@ -208,7 +208,7 @@ def cpu_baseline(si):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    B, N = 1, 128
+    B, N = 2, 1024
     times = {}
     for L in (1, 2):
         cfg = replace(si.CFG3, n_layers=L)
