@@ -10,6 +10,8 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ uint16_t f2bf(float f) {
@@ -26,6 +28,7 @@ struct Ep {
   void *out;
   int out_f32;
   int64_t ldc;
+  int vec_ok;  // out (and residual) rows allow 4-element vector accesses: ldc % 4 == 0, 16-byte aligned bases
 };
 
 template <int BF>
@@ -265,13 +268,240 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
   }
 }
 
+// ------------------------------------------------------------------------------- ping-pong MFMA kernel
+// 256x256 workgroup tile, 8 waves of 64x128, k walked in sub-tiles of 32.  The eight waves form two groups of
+// four (one wave of each group per SIMD) that run the same loop one phase apart: while one group issues the
+// 16 MFMAs of a sub-tile, the other reads its fragments of the next sub-tile from LDS and starts the global
+// loads three sub-tiles ahead, so the matrix pipe of every SIMD always has a wave feeding it.
+// Global loads go straight to LDS (buffer_load_dwordx4 ... lds: lane l of a wave writes 16 bytes at
+// base + 16 l), four stages of 32 KB.  Because that write pattern is fixed, bank conflicts are avoided by
+// permuting which 16-byte chunk of a row each lane fetches (an XOR swizzle) instead of by padding:
+//   k contiguous in memory:    LDS [256 rows][4 chunks];  chunk c of row r sits at position c ^ ((r >> 2) & 3)
+//   rows contiguous in memory: LDS [32 k][32 chunks];     chunk c of k-row k sits at position c ^ (4 (k & 3))
+namespace pp {
+
+constexpr int SK = 32;             // k extent of a sub-tile
+constexpr int OPB = 256 * SK * 2;  // bytes of one operand's sub-tile
+constexpr int STG = 2 * OPB;       // one stage: A sub-tile, then B sub-tile
+constexpr int NST = 4;
+typedef __attribute__((address_space(3))) void *lds_void;
+
+#define PP_WAIT_VM8_LGKM0 __builtin_amdgcn_s_waitcnt(0x0078)  // vmcnt(8) lgkmcnt(0)
+#define PP_WAIT_VM0 __builtin_amdgcn_s_waitcnt(0x0f70)        // vmcnt(0)
+
+template <int KM>
+struct Loader {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t off[2];  // byte offset of the lane's chunk in sub-tile 0 (kOob: outside the operand)
+  int kk[2];        // k of that chunk inside a sub-tile
+  uint32_t kstep;   // bytes from one sub-tile to the next
+  __device__ __forceinline__ void init(const uint16_t *base, int64_t ld, int rows_left, int K, int wave, int lane) {
+    const int64_t span = KM ? ((int64_t)(min(rows_left, 256) - 1) * ld + K) : ((int64_t)(K - 1) * ld + min(rows_left, (int)ld));
+    rsrc = make_rsrc(base, (uint32_t)(span * 2));
+    kstep = KM ? SK * 2 : (uint32_t)(SK * ld * 2);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int j = wave + 8 * i;  // which of the 16 one-KB pieces of the sub-tile
+      if (KM) {
+        const int r = 16 * j + (lane >> 2), c = (lane & 3) ^ ((r >> 2) & 3);
+        kk[i] = c * 8;
+        off[i] = r < rows_left ? (uint32_t)((r * ld + c * 8) * 2) : kOob;
+      } else {
+        const int k = 2 * j + (lane >> 5), c = (lane & 31) ^ (4 * (k & 3));
+        kk[i] = k;
+        off[i] = c * 8 < rows_left ? (uint32_t)((k * ld + c * 8) * 2) : kOob;
+      }
+    }
+  }
+  // start the loads of sub-tile u into the operand's 16 KB at dst (wave-uniform)
+  __device__ __forceinline__ void issue(int u, int K, char *dst, int wave) const {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t o = (u * SK + kk[i] < K) ? off[i] + u * kstep : kOob;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void)(dst + (wave + 8 * i) * 1024), 16, o, 0, 0, 0);
+    }
+  }
+};
+
+// Per-lane LDS byte offsets (inside an operand's sub-tile) of the fragment reads of a wave whose rows start at wb.
+template <int KM, int NTILE>
+struct Frags {
+  uint32_t a[KM ? 2 : NTILE];
+  __device__ __forceinline__ void init(int wb, int lane) {
+    const int c = lane & 31, g = lane >> 5, s = lane & 15, hi = (lane >> 4) & 1;
+    if (KM) {
+      a[0] = (uint32_t)((wb + c) * 64 + ((g ^ ((c >> 2) & 3)) * 16));
+      a[1] = a[0] ^ 32u;
+    } else {
+#pragma unroll
+      for (int i = 0; i < NTILE; ++i) {
+        const int chunk = (wb >> 3) + 4 * i + 2 * hi + ((s >> 1) & 1);
+        a[i] = (uint32_t)((g * 8 + (s >> 2)) * 512 + ((chunk ^ (4 * ((s >> 2) & 3))) * 16) + (s & 1) * 8);
+      }
+    }
+  }
+  // fragment of tile i (32 rows), k-step ks (16 wide) from the operand sub-tile at p
+  __device__ __forceinline__ bf16x8 get(const char *p, int i, int ks) const {
+    if (KM) return *reinterpret_cast<const bf16x8 *>(p + a[ks] + i * 2048);
+    typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+    const char *q = p + a[i] + ks * 8192;
+    s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q));
+    s16x4 y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 2048));
+    s16x8 v = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+template <int AKM, int BKM>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, Ep ep,
+                                                      int tiles_m, int tiles_n) {
+  constexpr int TM = 2, TN = 4;
+  constexpr int EPI_LD = 136;                    // floats per staged output row: 4 rows apart = 32 banks apart
+  constexpr int EPI_WAVE = 32 * EPI_LD * 4;      // one wave's 32 x 128 block of fp32 results
+  constexpr int SMEM = NST * STG > 8 * EPI_WAVE ? NST * STG : 8 * EPI_WAVE;
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+  const int nb = tiles_m * tiles_n;
+  int bid = blockIdx.x;
+  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;  // each XCD (own L2) gets a contiguous range of tiles
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * tiles_n;
+  const int grp = bid / per_group, first_m = grp * GROUP;
+  const int gsize = min(GROUP, tiles_m - first_m);
+  const int tile_m = first_m + (bid % per_group) % gsize, tile_n = (bid % per_group) / gsize;
+  const int m0 = tile_m * 256, n0 = tile_n * 256;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wpos = wave & 3, half = wave >> 2;  // waves w and w+4 share a SIMD and sit in different groups
+  const int wm = (wpos >> 1) * 128 + half * 64, wn = (wpos & 1) * 128;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Loader<AKM> la;
+  Loader<BKM> lb;
+  la.init(AKM ? A + (int64_t)m0 * lda : A + m0, lda, M - m0, K, wave, lane);
+  lb.init(BKM ? B + (int64_t)n0 * ldb : B + n0, ldb, N - n0, K, wave, lane);
+  Frags<AKM, TM> fa;
+  Frags<BKM, TN> fb;
+  fa.init(wm, lane);
+  fb.init(wn, lane);
+
+  const int nsub = (K + SK - 1) / SK;
+#pragma unroll
+  for (int u = 0; u < NST - 1; ++u) {
+    la.issue(u, K, smem + u * STG, wave);
+    lb.issue(u, K, smem + u * STG + OPB, wave);
+  }
+  PP_WAIT_VM8_LGKM0;  // sub-tile 0 has landed (4 loads per sub-tile and wave)
+  __builtin_amdgcn_s_barrier();
+  if (half) __builtin_amdgcn_s_barrier();  // the second group runs one phase late
+  for (int u = 0; u < nsub; ++u) {
+    const char *sa = smem + (u & (NST - 1)) * STG, *sb = sa + OPB;
+    char *dn = smem + ((u + NST - 1) & (NST - 1)) * STG;
+    __builtin_amdgcn_sched_barrier(0);
+    // memory phase: fragments of sub-tile u; global loads of sub-tile u + 3 into the stage both groups left last
+    // phase (beyond the last sub-tile the loads are out of range and just zero-fill)
+    bf16x8 af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[ks][i] = fa.get(sa, i, ks);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[ks][j] = fb.get(sb, j, ks);
+    }
+    la.issue(u + NST - 1, K, dn, wave);
+    lb.issue(u + NST - 1, K, dn + OPB, wave);
+    PP_WAIT_VM8_LGKM0;  // own fragments are in registers; own loads of sub-tile u + 1 have landed
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // compute phase
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+  }
+  if (!half) __builtin_amdgcn_s_barrier();
+  PP_WAIT_VM0;                   // own zero-filling loads beyond the last sub-tile
+  __builtin_amdgcn_s_barrier();  // ... and everybody else's: LDS is reused below
+
+  // Epilogue.  A 32x32 accumulator tile holds column lane % 32 and rows 8*(r/4) + 4*(lane/32) + r%4, which
+  // would store 2-byte pieces; each wave instead turns its results through LDS, 32 rows at a time, so that a
+  // lane owns 4 consecutive columns and a store instruction writes two full rows of 128 columns.
+  float *stage = reinterpret_cast<float *>(smem + wave * EPI_WAVE);
+  const int c = lane & 31, g = lane >> 5;
+  const int rows_left = M - m0;
+  const int ncol = n0 + wn + 4 * c;  // first of this lane's 4 columns
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  if (ep.bias) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (ncol + e < N) bias[e] = bf2f(static_cast<const uint16_t *>(ep.bias)[ncol + e]);
+  }
+  const bool vec = ep.vec_ok && ncol + 3 < N;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * EPI_LD + 32 * j + c] = acc[i][j][r];
+#pragma unroll 4
+    for (int p = 0; p < 16; ++p) {
+      const int row = 2 * p + g, ml = wm + 32 * i + row;
+      const f32x4 v4 = *reinterpret_cast<const f32x4 *>(stage + row * EPI_LD + 4 * c);
+      if (ml >= rows_left || ncol >= N) continue;
+      const int64_t o = (int64_t)(m0 + ml) * ep.ldc + ncol;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (v4[e] + bias[e]) * ep.alpha;
+      if (vec) {
+        if (ep.residual) {
+          const f32x4 rr = *reinterpret_cast<const f32x4 *>(ep.residual + o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += rr[e];
+        }
+        if (ep.out_f32) {
+          const f32x4 w = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4 *>(static_cast<float *>(ep.out) + o) = w;
+        } else {
+          const u32x2 w = {(uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16)};
+          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(ep.out) + o) = w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ncol + e >= N) break;
+          float x = v[e];
+          if (ep.residual) x += ep.residual[o + e];
+          if (ep.out_f32) static_cast<float *>(ep.out)[o + e] = x;
+          else static_cast<uint16_t *>(ep.out)[o + e] = f2bf(x);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace pp
+
 template <int AKM, int BKM>
 void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
   // 256x256 tiles (8 waves of 64x128) when they fill the chip, else 128x128 (4 waves of 64x64)
   const int big = ((M + 255) / 256) * ((N + 255) / 256);
   const char *force = getenv("TWIST_GEMM_TILE");  // test knob: "256" or "128" pins the tile size
   const bool use_big = force ? atoi(force) == 256 : big >= 200;
-  if (use_big) {
+  static const bool old_impl = getenv("TWIST_GEMM_OLD") != nullptr;  // test knob: the single-phase 256x256 kernel
+  if (use_big && !old_impl) {
+    const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+  } else if (use_big) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
     hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 256, 256, 4, 2>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
   } else {
@@ -301,7 +531,8 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
     twist_ctx *c; hipEvent_t e;
     ~StopRecorder() { if (e) (void)hipEventRecord(e, c->stream); }
   } stop_recorder{ctx, ev_stop};
-  Ep ep{e.alpha, e.bias, e.residual, e.out, e.out_f32, ldc};
+  Ep ep{e.alpha, e.bias, e.residual, e.out, e.out_f32, ldc, 0};
+  ep.vec_ok = ldc % 4 == 0 && aligned16(e.out) && (!e.residual || aligned16(e.residual));
   static const bool no_mfma = getenv("TWIST_NO_MFMA") != nullptr;
   // 16-byte chunks along k must not straddle the end of an operand row.  For y = x W with a ragged K the
   // caller pads x's rows (lda >= K rounded up to 8) with zeros; W's rows beyond K are never touched.
