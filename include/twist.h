@@ -201,6 +201,13 @@ TWIST_API twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M,
 TWIST_API twist_status twist_profile_gemm(twist_ctx *ctx, int32_t enable);
 TWIST_API twist_status twist_profile_gemm_read(twist_ctx *ctx, int64_t *launches, double *ms, double *flops);
 
+/* The weight-gradient projections of twist_subnet_fwd_bwd run on a second stream that the library creates
+ * (default priority), next to the input-gradient kernels on the context's stream; the call still returns with
+ * all of its work ordered before anything enqueued on the context's stream afterwards.  enable = 0 puts every
+ * kernel on the context's stream (needed when per-kernel durations are to be measured one at a time).
+ * Default: enabled. */
+TWIST_API twist_status twist_set_overlap(twist_ctx *ctx, int32_t enable);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,6 +82,7 @@ _SIGS = {
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
+    "twist_set_overlap": ([_vp, _i32], _i32),
     "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
 }
 for _name, (_args, _res) in _SIGS.items():
@@ -169,6 +170,9 @@ class Context:
         _check(lib.twist_gemm_raw(self.h, layout, M, N, K, _vp(A.data_ptr()), A.stride(0), _vp(B.data_ptr()), B.stride(0),
                                   _vp(out.data_ptr()), out.stride(0), int(out.dtype == torch.float32 and self.torch_dtype != torch.float32
                                                                           or out.dtype == torch.float32), alpha), self.h)
+
+    def twist_set_overlap(self, enable: bool) -> None:
+        _check(lib.twist_set_overlap(self.h, int(enable)), self.h)
 
     def twist_profile_gemm(self, enable: bool) -> None:
         _check(lib.twist_profile_gemm(self.h, int(enable)), self.h)

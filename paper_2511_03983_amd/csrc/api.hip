@@ -45,6 +45,11 @@ extern "C" twist_status twist_create(const twist_model_desc *desc, void *hip_str
 extern "C" void twist_destroy(twist_ctx *ctx) {
   if (!ctx) return;
   for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  for (int i = 0; i < 4; ++i) {
+    if (ctx->ev_ready[i]) (void)hipEventDestroy(ctx->ev_ready[i]);
+    if (ctx->ev_done[i]) (void)hipEventDestroy(ctx->ev_done[i]);
+  }
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
 }
 

@@ -168,16 +168,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_plain(const void *qkv, const
 
 }  // namespace
 
-twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh, bool *done);
-twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const void *o, const void *dout, const float *lse, float *delta,
+twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, bool *done);
+twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
                                       void *dqkv, int B, int N, int Hs, int dh, bool *done);
 
-twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh) {
+twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
   const float scale = 1.0f / sqrtf((float)dh);
   if (bf16) {
     bool done = false;
-    TW_TRY(twist_attention_fwd_mfma(ctx, qkv, o, lse, B, N, Hs, dh, &done));
+    TW_TRY(twist_attention_fwd_mfma(ctx, qkv, o, o32, lse, B, N, Hs, dh, &done));
     if (done) return TWIST_OK;
   }
   dim3 grid((unsigned)(((int64_t)B * Hs * N + 3) / 4)), block(256);
@@ -187,14 +187,14 @@ twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void
   return TWIST_OK;
 }
 
-twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const void *o, const void *dout, const float *lse, float *delta,
+twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
                                  void *dqkv, int B, int N, int Hs, int dh) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)(((int64_t)B * Hs * N + 3) / 4)), block(256);
   if (bf16) {
     bool done = false;
-    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o, dout, lse, delta, dqkv, B, N, Hs, dh, &done));
+    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, dh, &done));
     if (done) return TWIST_OK;
   }
   if (bf16) {

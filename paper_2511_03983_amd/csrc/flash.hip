@@ -12,8 +12,11 @@
 // products) stay row-major in LDS and are read with the transposing LDS load ds_read_tr16_b64, which hands
 // each lane 4 consecutive contraction rows of one column.
 //
-// delta_i = sum_j p_ij dp_ij is recomputed from p and dp in a first pass of the dQ kernel rather than taken
-// from the rounded output (see attention.hip).
+// delta_i = sum_j p_ij dp_ij equals dO_i . O_i.  The forward kernel therefore also writes its output unrounded
+// (fp32) and normalises by the sum of the probabilities AS ROUNDED for the matrix cores, so that O is an exact
+// convex combination of the value rows; the dQ kernel forms delta from that fp32 output in its prologue.  With
+// both in place a component common to all value rows (a large value bias) cancels exactly in p (dp - delta),
+// which it does not when delta is taken from the bf16-rounded output.
 #include "nn.h"
 
 namespace {
@@ -27,12 +30,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
-__device__ __forceinline__ uint32_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);  // finite inputs only
-  return u >> 16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// two floats to a packed pair of bf16, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) { return f2bf(a) | (f2bf(b) << 16); }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int r0) {
   u32x4 u = {pack2(v[r0], v[r0 + 1]), pack2(v[r0 + 2], v[r0 + 3]), pack2(v[r0 + 4], v[r0 + 5]), pack2(v[r0 + 6], v[r0 + 7])};
@@ -64,18 +69,29 @@ __device__ __forceinline__ void load_tile(uint16_t *lds, int ldl, const uint16_t
   }
 }
 
+// Causal work per query (or key) block grows linearly with its index, and all workgroups of a launch are
+// usually resident at once, two per CU (workgroup b and b + half land on the same CU).  Blocks are therefore
+// handed out in "snake" order: the first half of the grid takes the items from the most expensive down, the
+// second half from the cheapest up, so that the two workgroups sharing a CU add up to the same work.
+// Returns the rank of this workgroup's item in the list sorted by decreasing work.
+__device__ __forceinline__ int snake_rank(int b, int nwg) {
+  const int half = nwg >> 1;
+  return b < half ? b : nwg - 1 - (b - half);
+}
+
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
 // ------------------------------------------------------------------------------------------- forward
 // grid: (N/128) * B * Hs workgroups of 4 waves; wave w owns query rows [qb*128 + 32w, +32)
 template <int DH>
-__global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uint16_t *o, float *lse, int N, int Hs, float scale) {
+__global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
   constexpr int KS = DH / 16, MT = DH / 32, LDK = DH + 8, LDV = DH + 16;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LDK];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LDV];
-  const int nqb = N / 128;
-  const int qb = nqb - 1 - (int)(blockIdx.x % nqb);  // long rows first
-  const int bh = blockIdx.x / nqb, b = bh / Hs, h = bh % Hs;
+  const int nqb = N / 128, nbh = gridDim.x / nqb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - rank / nbh;  // late query blocks see the most keys
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
   const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
   const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
@@ -111,27 +127,32 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
       for (int mt = 0; mt < 2; ++mt) s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LDK + ks * 16 + g * 8), qf[ks], s[mt]);
     const bool diag = kt * 64 + 63 > q0;
     float mx = -INFINITY;
+    if (diag) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (kv > q) s[mt][r] = -INFINITY;
+        }
+    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float v = s[mt][r] * sc;
-        if (diag && kv > q) v = -INFINITY;
-        s[mt][r] = v;
-        mx = fmaxf(mx, v);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx);  // finite: key 0 is visible to every query and belongs to the first tile
+    const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
     const float alpha = exp2f(m - mn);
+    // probabilities, rounded to bf16 in pairs; the row sum is taken over the rounded values
+    uint32_t pk[2][8];
     float sum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[mt][r] - mn);
-        s[mt][r] = p;
-        sum += p;
+      for (int r = 0; r < 16; r += 2) {
+        const uint32_t u = pack2(exp2f(fmaf(s[mt][r], sc, -mn)), exp2f(fmaf(s[mt][r + 1], sc, -mn)));
+        pk[mt][r >> 1] = u;
+        sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
       }
     l = l * alpha + sum;
     m = mn;
@@ -144,7 +165,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const bf16x8 pf = pack8(s[mt], 8 * t);
+        const u32x4 pu = {pk[mt][4 * t], pk[mt][4 * t + 1], pk[mt][4 * t + 2], pk[mt][4 * t + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
 #pragma unroll
         for (int i = 0; i < MT; ++i)
           oacc[i] = MFMA(lds_frag_tr(Vs, LDV, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), pf, oacc[i]);
@@ -159,22 +181,27 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
     for (int j = 0; j < 4; ++j) {
       u32x2 w = {pack2(oacc[i][4 * j] * inv, oacc[i][4 * j + 1] * inv), pack2(oacc[i][4 * j + 2] * inv, oacc[i][4 * j + 3] * inv)};
       *reinterpret_cast<u32x2 *>(op + i * 32 + 8 * j + 4 * g) = w;
+      if (o32) {
+        const f32x4 w4 = {oacc[i][4 * j] * inv, oacc[i][4 * j + 1] * inv, oacc[i][4 * j + 2] * inv, oacc[i][4 * j + 3] * inv};
+        *reinterpret_cast<f32x4 *>(o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH + i * 32 + 8 * j + 4 * g) = w4;
+      }
     }
   if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------- backward: dQ (and delta)
-// Same decomposition as the forward kernel.  Pass 1 accumulates delta_q = sum_kv p dp; pass 2 forms
+// Same decomposition as the forward kernel.  delta_q = dO_q . O_q from the unrounded forward output, then
 // dS^T = p (dp - delta) scale and dQ^T[dh][q] += K^T[dh][kv] dS^T[kv][q].
 template <int DH>
-__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, float *delta, uint16_t *dqkv,
-                                                           int N, int Hs, float scale) {
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
+                                                           uint16_t *dqkv, int N, int Hs, float scale) {
   constexpr int KS = DH / 16, MT = DH / 32, LD = DH + 16;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LD];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LD];
-  const int nqb = N / 128;
-  const int qb = nqb - 1 - (int)(blockIdx.x % nqb);
-  const int bh = blockIdx.x / nqb, b = bh / Hs, h = bh % Hs;
+  const int nqb = N / 128, nbh = gridDim.x / nqb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - rank / nbh;  // late query blocks see the most keys
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
   const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
   const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
@@ -185,63 +212,61 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, 
 
   bf16x8 qf[KS], gf[KS];
   const uint16_t *gp = dout + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+  const float *op32 = o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+  float dl = 0.f;
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)q * ld + ks * 16 + g * 8);
     gf[ks] = *reinterpret_cast<const bf16x8 *>(gp + ks * 16 + g * 8);
+    const f32x4 oa = *reinterpret_cast<const f32x4 *>(op32 + ks * 16 + g * 8), ob = *reinterpret_cast<const f32x4 *>(op32 + ks * 16 + g * 8 + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dl += (float)gf[ks][e] * oa[e] + (float)gf[ks][e + 4] * ob[e];
   }
+  dl += __shfl_xor(dl, 32, 64);
+  if (g == 0) delta[((int64_t)b * Hs + h) * N + q] = dl;
   f32x16 acc[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  float dl = 0.f;
   const int n_tiles = (qb + 1) * 2;
-  for (int pass = 0; pass < 2; ++pass) {
-    for (int kt = 0; kt < n_tiles; ++kt) {
-      __syncthreads();
-      load_tile<64, DH>(Ks, LD, kp + (int64_t)kt * 64 * ld, ld);
-      load_tile<64, DH>(Vs, LD, vp + (int64_t)kt * 64 * ld, ld);
-      __syncthreads();
-      if (kt * 64 > q0 + 31) continue;
-      f32x16 s[2], dp[2];
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    __syncthreads();
+    load_tile<64, DH>(Ks, LD, kp + (int64_t)kt * 64 * ld, ld);
+    load_tile<64, DH>(Vs, LD, vp + (int64_t)kt * 64 * ld, ld);
+    __syncthreads();
+    if (kt * 64 > q0 + 31) continue;
+    f32x16 s[2], dp[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+      for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LD + ks * 16 + g * 8), qf[ks], s[mt]);
-          dp[mt] = MFMA(lds_frag(Vs + (mt * 32 + c) * LD + ks * 16 + g * 8), gf[ks], dp[mt]);
-        }
-      const bool diag = kt * 64 + 63 > q0;
+      for (int mt = 0; mt < 2; ++mt) {
+        s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LD + ks * 16 + g * 8), qf[ks], s[mt]);
+        dp[mt] = MFMA(lds_frag(Vs + (mt * 32 + c) * LD + ks * 16 + g * 8), gf[ks], dp[mt]);
+      }
+    const bool diag = kt * 64 + 63 > q0;
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          float p = exp2f(s[mt][r] * sc - L2);
-          if (diag && kv > q) p = 0.f;
-          if (pass == 0) dl += p * dp[mt][r];
-          else s[mt][r] = p * (dp[mt][r] - dl) * scale;
-        }
-      if (pass == 0) continue;
+      for (int r = 0; r < 16; ++r) {
+        const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        float p = exp2f(fmaf(s[mt][r], sc, -L2));
+        if (diag && kv > q) p = 0.f;
+        s[mt][r] = p * (dp[mt][r] - dl) * scale;
+      }
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 df = pack8(s[mt], 8 * t);
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 df = pack8(s[mt], 8 * t);
 #pragma unroll
-          for (int i = 0; i < MT; ++i)
-            acc[i] = MFMA(lds_frag_tr(Ks, LD, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), df, acc[i]);
-        }
-    }
-    if (pass == 0) {
-      dl += __shfl_xor(dl, 32, 64);
-      if (g == 0) delta[((int64_t)b * Hs + h) * N + q] = dl;
-    }
+        for (int i = 0; i < MT; ++i)
+          acc[i] = MFMA(lds_frag_tr(Ks, LD, mt * 32 + 16 * t + 4 * g, i * 32 + 16 * ((lane >> 4) & 1)), df, acc[i]);
+      }
   }
   uint16_t *op = dqkv + ((int64_t)b * N + q) * ld + (int64_t)h * DH;
 #pragma unroll
@@ -264,9 +289,10 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
   __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * LD];
   __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * LD];
   __shared__ __attribute__((aligned(16))) float Ls[64], Ds[64];
-  const int nkb = N / 128;
-  const int kb = blockIdx.x % nkb;  // early key blocks see the most queries: they come first
-  const int bh = blockIdx.x / nkb, b = bh / Hs, h = bh % Hs;
+  const int nkb = N / 128, nbh = gridDim.x / nkb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int kb = rank / nbh;  // early key blocks see the most queries
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
   const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
   const uint16_t *qp = qkv + (int64_t)b * N * ld + (int64_t)h * DH;
@@ -313,7 +339,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int ql = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);  // query row inside the tile
-        float p = exp2f(s[mt][r] * sc - Ls[ql]);
+        float p = exp2f(fmaf(s[mt][r], sc, -Ls[ql]));
         if (diag && qt * 64 + ql < kv) p = 0.f;
         dp[mt][r] = p * (dp[mt][r] - Ds[ql]) * scale;  // dS
         s[mt][r] = p;
@@ -349,35 +375,34 @@ bool shape_ok(const void *a, const void *b, int N, int Hs, int dh) {
 
 }  // namespace
 
-twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh, bool *done) {
+twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, bool *done) {
   static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
   *done = false;
   if (off || !shape_ok(qkv, o, N, Hs, dh)) return TWIST_OK;
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv);
-  if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), lse, N, Hs, scale);
-  else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), lse, N, Hs, scale);
+  if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
+  else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
   TW_HIP(ctx, hipGetLastError());
   *done = true;
   return TWIST_OK;
 }
 
-twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const void *o, const void *dout, const float *lse, float *delta, void *dqkv,
+twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta, void *dqkv,
                                       int B, int N, int Hs, int dh, bool *done) {
   static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
-  (void)o;
   *done = false;
-  if (off || !shape_ok(qkv, dout, N, Hs, dh) || (reinterpret_cast<uintptr_t>(dqkv) % 16)) return TWIST_OK;
+  if (off || !o32 || !shape_ok(qkv, dout, N, Hs, dh) || (reinterpret_cast<uintptr_t>(dqkv) % 16) || (reinterpret_cast<uintptr_t>(o32) % 16)) return TWIST_OK;
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv), *gout = static_cast<const uint16_t *>(dout);
   uint16_t *dx = static_cast<uint16_t *>(dqkv);
   if (dh == 128) {
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
   } else {
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
   }
   TW_HIP(ctx, hipGetLastError());

@@ -496,7 +496,7 @@ void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t
   // 256x256 tiles (8 waves of 64x128) when they fill the chip, else 128x128 (4 waves of 64x64)
   const int big = ((M + 255) / 256) * ((N + 255) / 256);
   const char *force = getenv("TWIST_GEMM_TILE");  // test knob: "256" or "128" pins the tile size
-  const bool use_big = force ? atoi(force) == 256 : big >= 200;
+  const bool use_big = force ? atoi(force) == 256 : big >= 64;
   static const bool old_impl = getenv("TWIST_GEMM_OLD") != nullptr;  // test knob: the single-phase 256x256 kernel
   if (use_big && !old_impl) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
@@ -515,8 +515,9 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 }  // namespace
 
 twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
-                        int64_t ldc, const GemmEpilogue &e) {
+                        int64_t ldc, const GemmEpilogue &e, hipStream_t st) {
   if (M <= 0 || N <= 0 || K <= 0) return TWIST_OK;
+  const hipStream_t stream = st ? st : stream;
   hipEvent_t ev_stop = nullptr;
   if (ctx->prof_gemm) {
     hipEvent_t ev_start;
@@ -525,12 +526,12 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
     ctx->prof_events.push_back(ev_start);
     ctx->prof_events.push_back(ev_stop);
     ctx->prof_flops += 2.0 * M * N * K;
-    TW_HIP(ctx, hipEventRecord(ev_start, ctx->stream));
+    TW_HIP(ctx, hipEventRecord(ev_start, stream));
   }
   struct StopRecorder {  // records the closing event on every return path
-    twist_ctx *c; hipEvent_t e;
-    ~StopRecorder() { if (e) (void)hipEventRecord(e, c->stream); }
-  } stop_recorder{ctx, ev_stop};
+    hipStream_t s; hipEvent_t e;
+    ~StopRecorder() { if (e) (void)hipEventRecord(e, s); }
+  } stop_recorder{stream, ev_stop};
   Ep ep{e.alpha, e.bias, e.residual, e.out, e.out_f32, ldc, 0};
   ep.vec_ok = ldc % 4 == 0 && aligned16(e.out) && (!e.residual || aligned16(e.residual));
   static const bool no_mfma = getenv("TWIST_NO_MFMA") != nullptr;
@@ -544,9 +545,9 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   if (vec_ok) {
     const uint16_t *a = static_cast<const uint16_t *>(A), *b = static_cast<const uint16_t *>(B);
     switch (lay) {
-      case GEMM_NT: launch_mfma<1, 1>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
-      case GEMM_NN: launch_mfma<1, 0>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
-      case GEMM_TN: launch_mfma<0, 0>(ctx->stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_NT: launch_mfma<1, 1>(stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_NN: launch_mfma<1, 0>(stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_TN: launch_mfma<0, 0>(stream, M, N, K, a, lda, b, ldb, ep); break;
     }
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
@@ -558,8 +559,8 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
     default: sam = 1; sak = lda; sbk = ldb; sbn = 1; break;
   }
   dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
-  if (bf16) hipLaunchKernelGGL(gemm_plain_kernel<1>, grid, block, 0, ctx->stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
-  else hipLaunchKernelGGL(gemm_plain_kernel<0>, grid, block, 0, ctx->stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
+  if (bf16) hipLaunchKernelGGL(gemm_plain_kernel<1>, grid, block, 0, stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
+  else hipLaunchKernelGGL(gemm_plain_kernel<0>, grid, block, 0, stream, M, N, K, A, sam, sak, B, sbk, sbn, ep);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }
@@ -575,6 +576,12 @@ extern "C" twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M
   e.out = C;
   e.out_f32 = out_f32;
   return twist_gemm(ctx, ctx->d.dtype == TWIST_BF16, (GemmLayout)layout, M, N, K, A, lda, B, ldb, ldc, e);
+}
+
+extern "C" twist_status twist_set_overlap(twist_ctx *ctx, int32_t enable) {
+  if (!ctx) TW_FAIL(nullptr, TWIST_EINVAL, "twist_set_overlap: null ctx");
+  ctx->overlap = enable != 0;
+  return TWIST_OK;
 }
 
 extern "C" twist_status twist_profile_gemm(twist_ctx *ctx, int32_t enable) {

@@ -18,13 +18,16 @@ enum GemmLayout {
 };
 
 // C[M,N] = epilogue( op(A) op(B) ), fp32 accumulation.  lda/ldb are the row strides of the stored operands.
+// `st`: stream to enqueue on (null: the context's stream).
 twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, int K, const void *A, int64_t lda, const void *B,
-                        int64_t ldb, int64_t ldc, const GemmEpilogue &ep);
+                        int64_t ldb, int64_t ldc, const GemmEpilogue &ep, hipStream_t st = nullptr);
 
-// causal multi-head attention on a fused qkv buffer [T, 3*Hs*dh] (q | k | v); o [T, Hs*dh]; lse [B,Hs,N] fp32
-twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh);
+// causal multi-head attention on a fused qkv buffer [T, 3*Hs*dh] (q | k | v); o [T, Hs*dh]; lse [B,Hs,N] fp32.
+// o32 (may be null): the same output unrounded, [T, Hs*dh] fp32, written by the tiled bf16 kernels only; the
+// tiled backward kernels need it (without it, or on shapes they do not cover, the plain kernels run).
+twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh);
 // dqkv [T, 3*Hs*dh] from do [T, Hs*dh]; delta [B,Hs,N] fp32 scratch (sum_j p_ij dp_ij, written by the dq pass)
-twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const void *o, const void *dout, const float *lse, float *delta,
+twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
                                  void *dqkv, int B, int N, int Hs, int dh);
 
 twist_status twist_embed_fwd(twist_ctx *ctx, int bf16, const int32_t *tok, const void *tok_embed, const void *pos_embed, float *x, int B, int N, int D, int vocab);

@@ -25,7 +25,7 @@ struct Carver {
 
 struct LayerBufs {
   void *h1, *qkv, *o, *h2, *gu, *a;
-  float *lse;
+  float *lse, *o32;  // o32: unrounded attention output (bf16 models), feeds the backward pass's delta
 };
 
 struct Workspace {
@@ -33,7 +33,7 @@ struct Workspace {
   std::vector<float *> stats; // (mean, rstd) per row for each norm
   std::vector<LayerBufs> layer;
   float *dx, *rope_tab, *rowloss, *partial, *delta;
-  void *dxb, *hf, *logits, *da, *dgu, *dh, *dout, *dqkv;
+  void *dxb, *dxb2, *hf, *logits, *da, *dgu, *dh, *dout, *dqkv;
   int64_t ld_logits;
   size_t bytes;
 };
@@ -58,6 +58,7 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
     b.h1 = c.take(T * D * es);
     b.qkv = c.take(T * 3 * HD * es);
     b.o = c.take(T * HD * es);
+    b.o32 = es == 2 ? c.take<float>(T * HD * 4) : nullptr;
     b.lse = c.take<float>((size_t)B * L.heads_sub[l] * N * 4);
     b.h2 = c.take(T * D * es);
     b.gu = c.take(T * nf * F * es);
@@ -65,6 +66,7 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
   }
   w.dx = c.take<float>(T * D * 4);
   w.dxb = c.take(T * D * es);
+  w.dxb2 = c.take(T * D * es);
   w.hf = c.take(T * D * es);
   w.ld_logits = (int64_t)align_up((size_t)d.vocab, 8);
   w.logits = d.vocab ? c.take(T * w.ld_logits * es) : nullptr;
@@ -80,6 +82,47 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
   w.dqkv = c.take(T * 3 * hd_max * es);
   w.bytes = align_up(c.off, 256);
 }
+
+// The weight-gradient projections of the backward pass only write parameter gradients, nothing downstream in
+// the pass reads them, and on their own most of them have too few output tiles to fill the chip.  They are
+// therefore enqueued on a second stream, where they run next to the chain of input-gradient kernels.  Slot i
+// (0 = FFN down, 1 = FFN up/gate, 2 = attention output, 3 = q/k/v) has a "ready" event (the main stream has
+// produced the operands) and a "done" event (the side stream has consumed them; the main stream waits for it
+// before it overwrites those operands one layer later).
+struct SideStream {
+  twist_ctx *ctx;
+  bool on = false, recorded[4] = {false, false, false, false};
+  twist_status init() {
+    on = ctx->overlap;
+    if (!on) return TWIST_OK;
+    if (!ctx->side) {
+      TW_HIP(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+      for (int i = 0; i < 4; ++i) {
+        TW_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_ready[i], hipEventDisableTiming));
+        TW_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_done[i], hipEventDisableTiming));
+      }
+    }
+    return TWIST_OK;
+  }
+  hipStream_t stream() const { return on ? ctx->side : nullptr; }
+  twist_status fork(int i) {  // everything enqueued on the main stream so far precedes the side stream's next kernel
+    if (!on) return TWIST_OK;
+    TW_HIP(ctx, hipEventRecord(ctx->ev_ready[i], ctx->stream));
+    TW_HIP(ctx, hipStreamWaitEvent(ctx->side, ctx->ev_ready[i], 0));
+    return TWIST_OK;
+  }
+  twist_status done(int i) {
+    if (!on) return TWIST_OK;
+    TW_HIP(ctx, hipEventRecord(ctx->ev_done[i], ctx->side));
+    recorded[i] = true;
+    return TWIST_OK;
+  }
+  twist_status wait_done(int i) {  // the main stream may overwrite slot i's operands after this
+    if (!on || !recorded[i]) return TWIST_OK;
+    TW_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_done[i], 0));
+    return TWIST_OK;
+  }
+};
 
 twist_status check_train_shape(twist_ctx *ctx, const twist_subnet *sub, int B, int N) {
   const twist_model_desc &d = ctx->d;
@@ -144,7 +187,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), P(L.at(l, TWIST_NORM1_B)), b.h1, w.stats[2 * l], T, D, d.norm_eps));
     TW_TRY(gemm(GEMM_NT, T, 3 * HD, D, b.h1, D, P(L.at(l, TWIST_WQ)), D, b.qkv, 3 * HD, 0, 1.f, P(L.at(l, TWIST_BQ))));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, b.qkv, w.rope_tab, B, N, Hs, dh, 1.f));
-    TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.lse, B, N, Hs, dh));
+    TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.o32, b.lse, B, N, Hs, dh));
     TW_TRY(gemm(GEMM_NT, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), HD, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), P(L.at(l, TWIST_NORM2_B)), b.h2, w.stats[2 * l + 1], T, D, d.norm_eps));
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
@@ -172,6 +215,14 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   }
 
   // ------------------------------------------------------------------------------------ backward through the layers
+  SideStream side{ctx};
+  TW_TRY(side.init());
+  auto wgrad = [&](int M, int Nn, const void *A, int64_t lda, const void *Bm, int64_t ldb, float *out, float alpha) {
+    GemmEpilogue e;
+    e.alpha = alpha; e.out = out; e.out_f32 = 1;
+    return twist_gemm(ctx, bf, GEMM_TN, M, Nn, T, A, lda, Bm, ldb, Nn, e, side.stream());
+  };
+  void *gx = w.dxb, *gx_other = w.dxb2;  // gradient of the residual stream in activation type: current, spare
   for (int l = d.n_layers - 1; l >= 0; --l) {
     const int Hs = L.heads_sub[l], HD = Hs * dh, F = L.ffn_sub[l] * d.ffn_granule;
     const float c_a = sub->plan->scale_mode ? sqrtf((float)d.n_heads / (float)Hs) : 1.f;
@@ -179,27 +230,41 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     const LayerBufs &b = w.layer[l];
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     // FFN branch: y = c_f (a W_down^T + b_down)
-    if (L.at(l, TWIST_B_DOWN).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dxb, D, c_f, G(L.at(l, TWIST_B_DOWN)), w.partial, T, D));
-    TW_TRY(gemm(GEMM_TN, D, F, T, w.dxb, D, b.a, F, G(L.at(l, TWIST_W_DOWN)), F, 1, c_f));
-    TW_TRY(gemm(GEMM_NN, T, F, D, w.dxb, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
+    if (L.at(l, TWIST_B_DOWN).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx, D, c_f, G(L.at(l, TWIST_B_DOWN)), w.partial, T, D));
+    TW_TRY(side.fork(0));
+    TW_TRY(wgrad(D, F, gx, D, b.a, F, G(L.at(l, TWIST_W_DOWN)), c_f));
+    TW_TRY(side.done(0));
+    TW_TRY(gemm(GEMM_NN, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
+    TW_TRY(side.wait_done(1));
     TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F));
     if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), w.partial, T, nf * F));
-    TW_TRY(gemm(GEMM_TN, nf * F, D, T, w.dgu, nf * F, b.h2, D, G(w1), D, 1));
+    TW_TRY(side.fork(1));
+    TW_TRY(wgrad(nf * F, D, w.dgu, nf * F, b.h2, D, G(w1), 1.f));
+    TW_TRY(side.done(1));
     TW_TRY(gemm(GEMM_NN, T, D, nf * F, w.dgu, nf * F, P(w1), D, w.dh, D, 0));
-    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), w.stats[2 * l + 1], w.dx, 1, w.dxb, G(L.at(l, TWIST_NORM2_W)),
+    TW_TRY(side.wait_done(2));
+    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), w.stats[2 * l + 1], w.dx, 1, gx_other, G(L.at(l, TWIST_NORM2_W)),
                           G(L.at(l, TWIST_NORM2_B)), w.partial, T, D));
     // attention branch: y = c_a (o C_attn^T + b_o)
-    if (L.at(l, TWIST_BO).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dxb, D, c_a, G(L.at(l, TWIST_BO)), w.partial, T, D));
-    TW_TRY(gemm(GEMM_TN, D, HD, T, w.dxb, D, b.o, HD, G(L.at(l, TWIST_WO)), HD, 1, c_a));
-    TW_TRY(gemm(GEMM_NN, T, HD, D, w.dxb, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
-    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh));
+    if (L.at(l, TWIST_BO).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx_other, D, c_a, G(L.at(l, TWIST_BO)), w.partial, T, D));
+    TW_TRY(side.fork(2));
+    TW_TRY(wgrad(D, HD, gx_other, D, b.o, HD, G(L.at(l, TWIST_WO)), c_a));
+    TW_TRY(side.done(2));
+    TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
+    TW_TRY(side.wait_done(3));
+    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, w.dqkv, w.rope_tab, B, N, Hs, dh, -1.f));
     if (L.at(l, TWIST_BQ).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dqkv, 3 * HD, 1.f, G(L.at(l, TWIST_BQ)), w.partial, T, 3 * HD));
-    TW_TRY(gemm(GEMM_TN, 3 * HD, D, T, w.dqkv, 3 * HD, b.h1, D, G(L.at(l, TWIST_WQ)), D, 1));
+    TW_TRY(side.fork(3));
+    TW_TRY(wgrad(3 * HD, D, w.dqkv, 3 * HD, b.h1, D, G(L.at(l, TWIST_WQ)), 1.f));
+    TW_TRY(side.done(3));
     TW_TRY(gemm(GEMM_NN, T, D, 3 * HD, w.dqkv, 3 * HD, P(L.at(l, TWIST_WQ)), D, w.dh, D, 0));
-    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), w.stats[2 * l], w.dx, 1, w.dxb, G(L.at(l, TWIST_NORM1_W)),
+    TW_TRY(side.wait_done(0));
+    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), w.stats[2 * l], w.dx, 1, gx, G(L.at(l, TWIST_NORM1_W)),
                           G(L.at(l, TWIST_NORM1_B)), w.partial, T, D));
   }
+  for (int i = 0; i < 4; ++i) TW_TRY(side.wait_done(i));  // join: the caller's stream sees the whole pass
+  (void)gx_other;
 
   if (lm) {
     // token embedding: rows used by this batch receive dx (on top of the projection gradient when tied)

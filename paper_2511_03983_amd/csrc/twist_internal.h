@@ -66,6 +66,11 @@ struct twist_ctx {
   bool prof_gemm = false;
   std::vector<hipEvent_t> prof_events;  // (start, stop) pairs
   double prof_flops = 0.0;
+  // second stream for the weight-gradient projections of the backward pass (created on first use, default
+  // priority) and the events that order it against `stream`; overlap can be switched off (twist_set_overlap)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_ready[4] = {}, ev_done[4] = {};
+  bool overlap = true;
   int esize() const { return d.dtype == TWIST_BF16 ? 2 : 4; }
   int n_ffn_units() const { return d.d_ff / d.ffn_granule; }
 };
