@@ -82,6 +82,11 @@ typedef struct {
   int32_t tied_head;   /* final projection shares the token embedding                                */
   int32_t use_rope;    /* rotary positions on Q,K (half-split pairing) instead of learned positions  */
   int32_t dtype;
+  int32_t out_unit_major; /* storage of the two output projections C^attn (TWIST_WO) and C^ffn (TWIST_W_DOWN), in the
+                           * central model and in every subnet.  0: [d_model, H*d_head] and [d_model, d_ff]
+                           * ([out, in] like every other matrix; their blocks are columns).  1: unit-major,
+                           * [H*d_head, d_model] and [d_ff, d_model] (the orientation of Section 2's C^attn): their
+                           * blocks are rows, so every partitioned tensor is gathered and averaged in whole rows. */
   float norm_eps, rope_theta;
 } twist_model_desc;
 

@@ -42,7 +42,7 @@ class TwistError(RuntimeError):
 
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "d_head", "d_ff", "ffn_granule", "vocab",
-                                         "max_seq", "act", "norm", "has_bias", "tied_head", "use_rope", "dtype")] + \
+                                         "max_seq", "act", "norm", "has_bias", "tied_head", "use_rope", "dtype", "out_unit_major")] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
@@ -100,7 +100,7 @@ def desc_from_cfg(cfg) -> ModelDesc:
     """Build a ModelDesc from any object with the model-shape attributes (see include/twist.h)."""
     return ModelDesc(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.d_head, cfg.d_ff, cfg.ffn_granule, cfg.vocab, cfg.max_seq,
                      ACT[cfg.act], NORM[cfg.norm], int(cfg.has_bias), int(cfg.tied_head), int(cfg.rope),
-                     BF16 if cfg.dtype == "bf16" else F32, cfg.norm_eps, cfg.rope_theta)
+                     BF16 if cfg.dtype == "bf16" else F32, int(getattr(cfg, "out_unit_major", False)), cfg.norm_eps, cfg.rope_theta)
 
 
 class Context:

@@ -135,13 +135,13 @@ twist_status generate_blueprint(twist_ctx *ctx, int n_full, int S, int n_sub, co
 
 // tensors and how the blueprint cuts them: kind, and whether blocks are rows (0) or columns (1)
 struct Cut { int kind; int axis; };
-const Cut *cut_of(int t) {
+const Cut *cut_of(const twist_model_desc &d, int t) {
   static const Cut head_rows{TWIST_KIND_HEAD, 0}, head_cols{TWIST_KIND_HEAD, 1}, ffn_rows{TWIST_KIND_FFN, 0}, ffn_cols{TWIST_KIND_FFN, 1};
   switch (t) {
     case TWIST_WQ: case TWIST_WK: case TWIST_WV: case TWIST_BQ: case TWIST_BK: case TWIST_BV: return &head_rows;
-    case TWIST_WO: return &head_cols;
+    case TWIST_WO: return d.out_unit_major ? &head_rows : &head_cols;
     case TWIST_W_GATE: case TWIST_W_UP: case TWIST_B_UP: return &ffn_rows;
-    case TWIST_W_DOWN: return &ffn_cols;
+    case TWIST_W_DOWN: return d.out_unit_major ? &ffn_rows : &ffn_cols;
     default: return nullptr;
   }
 }
@@ -172,9 +172,9 @@ void full_shape(const twist_model_desc &d, int t, int &rows, int &cols) {
   const int hd = d.n_heads * d.d_head;
   switch (t) {
     case TWIST_WQ: case TWIST_WK: case TWIST_WV: rows = hd; cols = d.d_model; break;
-    case TWIST_WO: rows = d.d_model; cols = hd; break;
+    case TWIST_WO: rows = d.d_model; cols = hd; if (d.out_unit_major) std::swap(rows, cols); break;
     case TWIST_W_GATE: case TWIST_W_UP: rows = d.d_ff; cols = d.d_model; break;
-    case TWIST_W_DOWN: rows = d.d_model; cols = d.d_ff; break;
+    case TWIST_W_DOWN: rows = d.d_model; cols = d.d_ff; if (d.out_unit_major) std::swap(rows, cols); break;
     case TWIST_BQ: case TWIST_BK: case TWIST_BV: rows = hd; cols = 1; break;
     case TWIST_B_UP: rows = d.d_ff; cols = 1; break;
     default: rows = d.d_model; cols = 1; break;
@@ -205,7 +205,7 @@ void build_layout(const twist_ctx *ctx, twist_plan *plan) {
                                       {TWIST_NORM1_W, -1, -1}, {TWIST_NORM1_B, -1, -1}, {TWIST_NORM2_W, -1, -1}, {TWIST_NORM2_B, -1, -1}};
   auto sub_shape = [&](int l, int t, int &rows, int &cols) {
     full_shape(d, t, rows, cols);
-    if (const Cut *c = cut_of(t)) {
+    if (const Cut *c = cut_of(d, t)) {
       const PlanEntry &pe = plan->at(l, c->kind);
       const int q = c->kind == TWIST_KIND_HEAD ? d.d_head : d.ffn_granule;
       (c->axis == 0 ? rows : cols) = pe.n_sub * q;
@@ -347,7 +347,7 @@ bool make_job(const twist_ctx *ctx, const twist_plan *plan, int l, int t, const 
   const int VN = 16 / es;
   jb.full = full_ptr;
   jb.sub_off = slot.off;
-  const Cut *c = l >= 0 ? cut_of(t) : nullptr;
+  const Cut *c = l >= 0 ? cut_of(d, t) : nullptr;
   int frows, fcols;
   if (l >= 0) full_shape(d, t, frows, fcols); else global_shape(d, t, frows, fcols);
   if (c) {

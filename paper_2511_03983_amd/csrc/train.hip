@@ -161,6 +161,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   const int rms = d.norm == TWIST_NORM_RMS;
   const int nf = d.act == TWIST_ACT_SWIGLU ? 2 : 1;
   const bool lm = d.vocab > 0;
+  const bool um = d.out_unit_major != 0;  // output projections stored [in, out]: the three GEMM forms rotate
   auto P = [&](const Slot &s) -> void * { return s.off < 0 ? nullptr : sub->params + s.off * es; };
   auto G = [&](const Slot &s) -> float * { return s.off < 0 ? nullptr : sub->grads + s.off; };
   auto gemm = [&](GemmLayout lay, int M, int Nn, int K, const void *A, int64_t lda, const void *Bm, int64_t ldb, void *out, int64_t ldc, int out_f32,
@@ -188,12 +189,14 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(gemm(GEMM_NT, T, 3 * HD, D, b.h1, D, P(L.at(l, TWIST_WQ)), D, b.qkv, 3 * HD, 0, 1.f, P(L.at(l, TWIST_BQ))));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, b.qkv, w.rope_tab, B, N, Hs, dh, 1.f));
     TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.o32, b.lse, B, N, Hs, dh));
-    TW_TRY(gemm(GEMM_NT, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), HD, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
+    if (um) TW_TRY(gemm(GEMM_NN, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), D, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
+    else TW_TRY(gemm(GEMM_NT, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), HD, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), P(L.at(l, TWIST_NORM2_B)), b.h2, w.stats[2 * l + 1], T, D, d.norm_eps));
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     TW_TRY(gemm(GEMM_NT, T, nf * F, D, b.h2, D, P(w1), D, b.gu, nf * F, 0, 1.f, P(L.at(l, TWIST_B_UP))));
     TW_TRY(twist_act_fwd(ctx, bf, d.act, b.gu, b.a, T, F));
-    TW_TRY(gemm(GEMM_NT, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), F, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
+    if (um) TW_TRY(gemm(GEMM_NN, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), D, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
+    else TW_TRY(gemm(GEMM_NT, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), F, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
   }
 
   // ------------------------------------------------------------------------------------ loss and its gradient
@@ -232,9 +235,11 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     // FFN branch: y = c_f (a W_down^T + b_down)
     if (L.at(l, TWIST_B_DOWN).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx, D, c_f, G(L.at(l, TWIST_B_DOWN)), w.partial, T, D));
     TW_TRY(side.fork(0));
-    TW_TRY(wgrad(D, F, gx, D, b.a, F, G(L.at(l, TWIST_W_DOWN)), c_f));
+    if (um) TW_TRY(wgrad(F, D, b.a, F, gx, D, G(L.at(l, TWIST_W_DOWN)), c_f));
+    else TW_TRY(wgrad(D, F, gx, D, b.a, F, G(L.at(l, TWIST_W_DOWN)), c_f));
     TW_TRY(side.done(0));
-    TW_TRY(gemm(GEMM_NN, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
+    if (um) TW_TRY(gemm(GEMM_NT, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), D, w.da, F, 0, c_f));
+    else TW_TRY(gemm(GEMM_NN, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
     TW_TRY(side.wait_done(1));
     TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F));
     if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), w.partial, T, nf * F));
@@ -248,9 +253,11 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     // attention branch: y = c_a (o C_attn^T + b_o)
     if (L.at(l, TWIST_BO).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx_other, D, c_a, G(L.at(l, TWIST_BO)), w.partial, T, D));
     TW_TRY(side.fork(2));
-    TW_TRY(wgrad(D, HD, gx_other, D, b.o, HD, G(L.at(l, TWIST_WO)), c_a));
+    if (um) TW_TRY(wgrad(HD, D, b.o, HD, gx_other, D, G(L.at(l, TWIST_WO)), c_a));
+    else TW_TRY(wgrad(D, HD, gx_other, D, b.o, HD, G(L.at(l, TWIST_WO)), c_a));
     TW_TRY(side.done(2));
-    TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
+    if (um) TW_TRY(gemm(GEMM_NT, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), D, w.dout, HD, 0, c_a));
+    else TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
     TW_TRY(side.wait_done(3));
     TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, w.dqkv, w.rope_tab, B, N, Hs, dh, -1.f));

@@ -8,7 +8,8 @@ identical inputs without either seeing the other's code.
 
 Shapes follow the GPT-style workloads of the paper's experiments (Section 5,
 "Setup": 12-layer / 12-head / 768-wide GPT-2, 1024-token sequences) and their
-Llama-shaped scale-ups; layouts are [out_features, in_features] row-major.
+Llama-shaped scale-ups; layouts are [out_features, in_features] row-major (the mathematical
+shapes; `stored_shapes` gives the memory layout a configuration asks the library to use).
 """
 from __future__ import annotations
 
@@ -43,6 +44,7 @@ class ModelCfg:
     dtype: str = "f32"          # "f32" | "bf16"
     norm_eps: float = 1e-5
     rope_theta: float = 10000.0
+    out_unit_major: bool = False  # the library stores wo and w_down transposed ([in, out]); the maths is unchanged
 
     @property
     def n_ffn_units(self) -> int:
@@ -94,6 +96,18 @@ def layer_shapes(cfg: ModelCfg) -> dict:
         s["norm2_b"] = (d,)
     if cfg.has_bias:
         s.update(bq=(hd,), bk=(hd,), bv=(hd,), bo=(d,), b_up=(f,), b_down=(d,))
+    return s
+
+
+STORED_TRANSPOSED = ("wo", "w_down")
+
+
+def stored_shapes(cfg: ModelCfg) -> dict:
+    """Shapes as the library stores them: with `out_unit_major` the two output projections are kept transposed."""
+    s = layer_shapes(cfg)
+    if cfg.out_unit_major:
+        for k in STORED_TRANSPOSED:
+            s[k] = s[k][::-1]
     return s
 
 

@@ -9,11 +9,17 @@ def torch_dtype(cfg):
     return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
 
 
+def _stored(cfg, k, a):
+    """[out, in] array <-> the layout the library keeps it in (a transpose for the output projections of a
+    unit-major configuration; its own inverse)."""
+    return a.T if cfg.out_unit_major and k in si.STORED_TRANSPOSED else a
+
+
 def to_device(full_np, cfg):
-    """numpy fp64 model (values already on the dtype's grid) -> dict of CUDA tensors."""
+    """numpy fp64 model (values already on the dtype's grid) -> dict of CUDA tensors in the stored layout."""
     dt = torch_dtype(cfg)
-    conv = lambda a: torch.tensor(a, dtype=torch.float64).to(dt).cuda().contiguous()
-    return {"layers": [{k: conv(v) for k, v in lw.items()} for lw in full_np["layers"]],
+    conv = lambda a: torch.tensor(np.ascontiguousarray(a), dtype=torch.float64).to(dt).cuda().contiguous()
+    return {"layers": [{k: conv(_stored(cfg, k, v)) for k, v in lw.items()} for lw in full_np["layers"]],
             "globals": {k: conv(v) for k, v in full_np["globals"].items()}}
 
 
@@ -21,16 +27,18 @@ def to_numpy(t):
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-def model_to_numpy(full_t):
-    return {"layers": [{k: to_numpy(v) for k, v in lw.items()} for lw in full_t["layers"]],
+def model_to_numpy(full_t, cfg=None):
+    """Device model back to [out, in] numpy arrays."""
+    back = (lambda k, a: _stored(cfg, k, a)) if cfg is not None else (lambda k, a: a)
+    return {"layers": [{k: back(k, to_numpy(v)) for k, v in lw.items()} for lw in full_t["layers"]],
             "globals": {k: to_numpy(v) for k, v in full_t["globals"].items()}}
 
 
 def subnet_to_numpy(sub, cfg, what=0):
-    """Read every tensor of a library subnet back through twist_subnet_view, in the oracle's nesting."""
+    """Read every tensor of a library subnet back through twist_subnet_view, in the oracle's nesting and [out, in]."""
     out = {"layers": [], "globals": {}}
     for l in range(cfg.n_layers):
-        out["layers"].append({k: to_numpy(sub.twist_subnet_view(l, k, what)) for k in si.layer_shapes(cfg)})
+        out["layers"].append({k: _stored(cfg, k, to_numpy(sub.twist_subnet_view(l, k, what))) for k in si.layer_shapes(cfg)})
     for k in si.global_shapes(cfg):
         out["globals"][k] = to_numpy(sub.twist_subnet_view(-1, k, what))
     return out

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from helpers import bf16_ulp_distance, model_to_numpy, rel_fro, subnet_to_numpy, to_device, to_numpy
+from helpers import _stored, bf16_ulp_distance, model_to_numpy, rel_fro, subnet_to_numpy, to_device, to_numpy
 from oracle import move as omove
 from oracle.sample import sample_plan
 
@@ -73,6 +73,9 @@ SMALL = {
     "ragged_f32": (si.ModelCfg(n_layers=2, d_model=36, n_heads=5, d_head=6, d_ff=70, ffn_granule=7, vocab=19, max_seq=8), 3, 2, 4),
     "ragged_bf16": (si.ModelCfg(n_layers=1, d_model=100, n_heads=3, d_head=10, d_ff=99, ffn_granule=1, vocab=0, dtype="bf16"), 2, 2, 60),
 }
+# the same shapes with the output projections stored unit-major (every partitioned tensor cut along rows)
+for _k in ("cfg1_f32", "gpt_bf16", "llama_bf16", "llama_overlap_S8", "ragged_f32", "ragged_bf16"):
+    SMALL[_k + "_um"] = (replace(SMALL[_k][0], out_unit_major=True),) + SMALL[_k][1:]
 
 
 def _setup(lib, name, seed=0, **kw):
@@ -109,8 +112,8 @@ def _perturb(cfg, sub, s, seed=5):
     for l in range(cfg.n_layers):
         for k in si.layer_shapes(cfg):
             v = sub.twist_subnet_view(l, k)
-            n = si.perturbation(seed, f"{s}.{l}.{k}", tuple(v.shape))
-            v.add_(torch.tensor(n, dtype=torch.float64).to(v.dtype).cuda())
+            n = si.perturbation(seed, f"{s}.{l}.{k}", tuple(_stored(cfg, k, v).shape))     # drawn in [out, in]
+            v.add_(torch.tensor(np.ascontiguousarray(_stored(cfg, k, n)), dtype=torch.float64).to(v.dtype).cuda())
     for k in si.global_shapes(cfg):
         v = sub.twist_subnet_view(-1, k)
         v.add_(torch.tensor(si.perturbation(seed, f"{s}.g.{k}", tuple(v.shape)), dtype=torch.float64).to(v.dtype).cuda())
@@ -130,7 +133,7 @@ def test_aggregate_matches_formula(lib, name, drop):
     sub_np = {s: subnet_to_numpy(subs[s], cfg) for s in use}
     want = omove.aggregate(full_np, oplan, sub_np, cfg.d_head, cfg.ffn_granule)
     ctx.twist_aggregate(plan, [subs[s] for s in use], fw)
-    got = model_to_numpy(full_t)
+    got = model_to_numpy(full_t, cfg)
     tol = 5e-3 if cfg.dtype == "bf16" else 1e-4
     for l in range(cfg.n_layers):
         for k, w in want["layers"][l].items():
@@ -157,10 +160,10 @@ def test_aggregate_matches_formula(lib, name, drop):
 
 def test_untrained_partition_roundtrip_is_bit_exact(lib):
     cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "gpt_bf16", seed=6)     # 12 = 4*3 heads, 3072 = 4*768
-    before = model_to_numpy(full_t)
+    before = model_to_numpy(full_t, cfg)
     subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
     ctx.twist_aggregate(plan, subs, fw)
-    after = model_to_numpy(full_t)
+    after = model_to_numpy(full_t, cfg)
     for l in range(cfg.n_layers):
         for k in before["layers"][l]:
             assert np.array_equal(before["layers"][l][k], after["layers"][l][k]), k
@@ -168,32 +171,34 @@ def test_untrained_partition_roundtrip_is_bit_exact(lib):
         assert np.array_equal(before["globals"][k], after["globals"][k]), k
 
 
-def test_aggregate_is_deterministic(lib):
-    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "llama_overlap_S8", seed=8)
+@pytest.mark.parametrize("name", ["llama_overlap_S8", "llama_overlap_S8_um"])
+def test_aggregate_is_deterministic(lib, name):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=8)
     subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
     for s, sub in enumerate(subs):
         _perturb(cfg, sub, s)
     ctx.twist_aggregate(plan, subs, fw)
-    first = model_to_numpy(full_t)
+    first = model_to_numpy(full_t, cfg)
     for l, lw in enumerate(full_np["layers"]):          # reset and repeat
         for k, v in lw.items():
-            full_t["layers"][l][k].copy_(torch.tensor(v, dtype=torch.float64))
+            full_t["layers"][l][k].copy_(torch.tensor(np.ascontiguousarray(_stored(cfg, k, v)), dtype=torch.float64))
     ctx.twist_aggregate(plan, subs, fw)
-    second = model_to_numpy(full_t)
+    second = model_to_numpy(full_t, cfg)
     for l in range(cfg.n_layers):
         for k in first["layers"][l]:
             assert np.array_equal(first["layers"][l][k], second["layers"][l][k])
 
 
-def test_deployment_extract_leaves_uncovered_units_alone(lib):
-    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "llama_bf16", seed=9, require_coverage=False)
+@pytest.mark.parametrize("name", ["llama_bf16", "llama_bf16_um"])
+def test_deployment_extract_leaves_uncovered_units_alone(lib, name):
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=9, require_coverage=False)
     subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
     for s, sub in enumerate(subs):
         _perturb(cfg, sub, s)
     sub_np = {s: subnet_to_numpy(subs[s], cfg) for s in range(S)}
     want = omove.aggregate(full_np, oplan, sub_np, cfg.d_head, cfg.ffn_granule)
     ctx.twist_aggregate(plan, subs, fw)
-    got = model_to_numpy(full_t)
+    got = model_to_numpy(full_t, cfg)
     cnt = np.array(oplan[0][1]["count"])
     assert (cnt == 0).any()                                 # some neurons really have no owner
     for k in ("w_up", "w_gate"):
@@ -204,13 +209,14 @@ def test_deployment_extract_leaves_uncovered_units_alone(lib):
 
 
 # ------------------------------------------------------------------------------------------ full-size shapes
-def test_workload4_layer_shape_sampled_rows(lib):
+@pytest.mark.parametrize("unit_major", [False, True])
+def test_workload4_layer_shape_sampled_rows(lib, unit_major):
     """Two layers at the full Llama-7B layer shape, S = 8, in the launch configuration the benchmark times.
     Weights are drawn on the device; the checker recomputes sampled rows and columns from the same values."""
-    cfg = replace(si.CFG4, n_layers=2)
+    cfg = replace(si.CFG4, n_layers=2, out_unit_major=unit_major)
     S, hs, fs = 8, 16, 5504
     gen = torch.Generator(device="cuda").manual_seed(4)
-    layers = [{k: (torch.randn(shp, generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for k, shp in si.layer_shapes(cfg).items()}
+    layers = [{k: (torch.randn(shp, generator=gen, device="cuda") * 0.02).to(torch.bfloat16) for k, shp in si.stored_shapes(cfg).items()}
               for _ in range(cfg.n_layers)]
     fw = lib.FullWeights(layers)
     ctx = _ctx(lib, cfg)
@@ -221,17 +227,25 @@ def test_workload4_layer_shape_sampled_rows(lib):
     l = 1
     heads = [oplan[l][0]["idx"][s] for s in range(S)]
     units = [np.array(oplan[l][1]["idx"][s]) for s in range(S)]
+    # axis along which a stored tensor is cut: the checker's table, except that unit-major storage turns the
+    # column cuts of the two output projections into row cuts
+    def cut(name):
+        ka = omove.PARTITIONED.get(name)
+        if ka is None:
+            return None
+        return (ka[0], 0) if unit_major and name in si.STORED_TRANSPOSED else ka
     # extract: sampled rows / columns of each partitioned tensor are exact copies
     for s in (0, 5, 7):
         e_head = omove.element_index(heads[s], cfg.d_head)
-        for name, e in (("wq", e_head), ("wv", e_head), ("w_up", units[s]), ("w_gate", units[s])):
-            rows = rng.integers(0, len(e), 16)
-            got = subs[s].twist_subnet_view(l, name)[torch.tensor(rows).cuda()]
-            assert torch.equal(got, layers[l][name][torch.tensor(e[rows]).cuda()]), (s, name)
-        for name, e in (("wo", e_head), ("w_down", units[s])):
-            rows = torch.tensor(rng.integers(0, cfg.d_model, 8)).cuda()
-            got = subs[s].twist_subnet_view(l, name)[rows]
-            assert torch.equal(got, layers[l][name][rows][:, torch.tensor(e).cuda()]), (s, name)
+        for name, e in (("wq", e_head), ("wv", e_head), ("w_up", units[s]), ("w_gate", units[s]), ("wo", e_head), ("w_down", units[s])):
+            if cut(name)[1] == 0:
+                rows = rng.integers(0, len(e), 16)
+                got = subs[s].twist_subnet_view(l, name)[torch.tensor(rows).cuda()]
+                assert torch.equal(got, layers[l][name][torch.tensor(e[rows]).cuda()]), (s, name)
+            else:
+                rows = torch.tensor(rng.integers(0, cfg.d_model, 8)).cuda()
+                got = subs[s].twist_subnet_view(l, name)[rows]
+                assert torch.equal(got, layers[l][name][rows][:, torch.tensor(e).cuda()]), (s, name)
     # train stand-in, then aggregate; check sampled rows against the formula evaluated in fp64
     for s, sub in enumerate(subs):
         for name in si.layer_shapes(cfg):
@@ -240,7 +254,7 @@ def test_workload4_layer_shape_sampled_rows(lib):
     old = {k: v.clone() for k, v in layers[l].items()}
     ctx.twist_aggregate(plan, subs, fw)
     for name in ("wk", "w_up", "wo", "w_down", "norm1_w"):
-        kind_axis = omove.PARTITIONED.get(name)
+        kind_axis = cut(name)
         full_rows = rng.integers(0, layers[l][name].shape[0], 6)
         for r in full_rows:
             r = int(r)
