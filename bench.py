@@ -43,7 +43,7 @@ def device_weights(cfg, seed, si, torch):
             out[r:r + n] = (torch.randn((n, shp[1]), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
         return out
 
-    layers = [{k: draw(k, s) for k, s in si.layer_shapes(cfg).items()} for _ in range(cfg.n_layers)]
+    layers = [{k: draw(k, s) for k, s in si.stored_shapes(cfg).items()} for _ in range(cfg.n_layers)]
     globs = {k: draw(k, s) for k, s in si.global_shapes(cfg).items()}
     return layers, globs
 
@@ -59,7 +59,7 @@ def flops_fwd_bwd(cfg, hs, F, B, N):
 
 
 def bench_train(args, tw, si, torch):
-    cfg = si.CFG3
+    cfg = replace(si.CFG3, out_unit_major=True)      # output projections stored unit-major: every gather is a row gather
     S, hs, fs, B, N = 4, 8, 2816, 4, 2048
     log(f"[bench] workload llama1b_round: L={cfg.n_layers} d={cfg.d_model} H'={hs} F'={fs} S={S} B={B} N={N} local_steps={args.local_steps}")
     layers, globs = device_weights(cfg, 0, si, torch)
@@ -115,7 +115,6 @@ def bench_train(args, tw, si, torch):
     for w in range(args.warmup):
         one_round(w, False)
         log(f"[bench] warmup round {w} done, loss {loss.item():.4f}")
-    ctx.twist_profile_gemm(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -123,8 +122,22 @@ def bench_train(args, tw, si, torch):
         log(f"[bench] timed round {k} done, loss {loss.item():.4f}")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # Per-launch durations of the projection kernel: one more forward+backward per subnet with every kernel on
+    # one stream (in the timed region the weight-gradient projections overlap other kernels on a second stream,
+    # where a launch's own duration says little), each launch bracketed by HIP events on that stream.
+    plan = ctx.twist_sample(S, hs, fs, seed=0, rnd=args.warmup + args.steps)
+    subs = [ctx.twist_extract(plan, fw, s, store=tw.STORE_ADAMW, storage=stor[s]) for s in range(S)]
+    ctx.twist_set_overlap(False)
+    ctx.twist_subnet_fwd_bwd(subs[0], xs[0], ys[0], ws, loss)
+    ctx.twist_profile_gemm(True)
+    for s, sub in enumerate(subs):
+        ctx.twist_subnet_fwd_bwd(sub, xs[s * args.local_steps], ys[s * args.local_steps], ws, loss)
     n_gemm, gemm_ms, gemm_flops = ctx.twist_profile_gemm_read()
     ctx.twist_profile_gemm(False)
+    ctx.twist_set_overlap(True)
+    for sub in subs:
+        sub.close()
+    plan.close()
     tokens = args.steps * S * args.local_steps * B * N
     fb_calls = args.steps * S * args.local_steps
     fb_ms = phase_ms["fwd_bwd"] / fb_calls
@@ -143,9 +156,9 @@ def bench_train(args, tw, si, torch):
     return res
 
 
-def bench_movers(args, tw, si, torch):
+def bench_movers(args, tw, si, torch, unit_major=True):
     """extract x8 and aggregate at the Llama-7B layer-stack shape (memory-bound)."""
-    cfg = si.CFG4
+    cfg = replace(si.CFG4, out_unit_major=unit_major)
     S, hs, fs = 8, 16, 5504
     layers, _ = device_weights(cfg, 1, si, torch)
     fw = tw.FullWeights(layers)
@@ -193,6 +206,8 @@ def bench_movers(args, tw, si, torch):
         y.copy_(x)
     b = ev(); b.record(); torch.cuda.synchronize()
     res["copy_ceiling_GBps"] = 2 * x.numel() * 5 / a.elapsed_time(b) / 1e6
+    del x, y, stor, layers, fw
+    torch.cuda.empty_cache()
     return res
 
 
@@ -247,8 +262,10 @@ def main():
 
     train = bench_train(args, tw, si, torch)
     log("[bench] train:", json.dumps(train))
-    movers = None if args.skip_movers else bench_movers(args, tw, si, torch)
-    log("[bench] movers:", json.dumps(movers))
+    movers = None if args.skip_movers else bench_movers(args, tw, si, torch, unit_major=True)
+    log("[bench] movers (unit-major output projections):", json.dumps(movers))
+    movers_rm = None if args.skip_movers else bench_movers(args, tw, si, torch, unit_major=False)
+    log("[bench] movers ([out, in] output projections):", json.dumps(movers_rm))
     cpu = None if args.skip_cpu else cpu_baseline(si)
 
     g = train["gemm"]
@@ -258,9 +275,11 @@ def main():
         "ms_per_step": train["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "llama1b_round: configs[2], 22 layers d=2048 16x128 heads SwiGLU 5632 vocab 32000, S=4 overlapping half-width "
-                               f"subnets, batch 4x2048 Zipf(1.1) tokens, {args.local_steps} local AdamW steps per subnet, sample+extract+train+aggregate",
+                               f"subnets, batch 4x2048 Zipf(1.1) tokens, {args.local_steps} local AdamW steps per subnet, sample+extract+train+aggregate; "
+                               "output projections stored unit-major",
                    "S": 4, "batch": 4, "seq_len": 2048, "local_steps": args.local_steps},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (all projection launches of the timed region)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_pp_kernel / gemm_mfma_kernel: every projection launch of one forward+backward per subnet, "
+                                                 "kernels serialised on one stream",
                      "achieved": g["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g["tflops"] / PEAK_BF16_TFLOPS,
                      "traffic": None, "avg_launch_ms": g["avg_ms"], "launches": g["launches"], "flops_per_launch": g["flops_per_launch"]},
         "fwd_bwd": {"tokens_per_s": train["fwd_bwd_tokens_per_s"], "ms": train["fwd_bwd_ms"], "tflops": train["fwd_bwd_tflops"],
@@ -271,11 +290,12 @@ def main():
     if movers:
         out["movers_llama7b_stack"] = movers
         out["roofline_movers"] = {
-            "bound": "hbm", "kernel": "extract_kernel / aggregate_kernel at configs[3] (32 layers d=4096, S=8, 50%)",
+            "bound": "hbm", "kernel": "extract_kernel / aggregate_rows_kernel at configs[3] (32 layers d=4096, S=8, 50%), output projections unit-major",
             "achieved": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) / ((movers["extract_ms"] + movers["aggregate_ms"]) * 1e-3),
             "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) / ((movers["extract_ms"] + movers["aggregate_ms"]) * 1e-3) / PEAK_HBM_GBS,
             "traffic": None}
+        out["movers_llama7b_stack_out_in_layout"] = movers_rm
     print(json.dumps(out), flush=True)
 
 

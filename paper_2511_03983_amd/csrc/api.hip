@@ -339,7 +339,7 @@ extern "C" twist_status twist_subnet_bytes(twist_ctx *ctx, const twist_plan *pla
 namespace {
 
 // Describe tensor t of layer l (or global t when l < 0) as a MoveJob; returns false if the model lacks it.
-bool make_job(const twist_ctx *ctx, const twist_plan *plan, int l, int t, const void *full_ptr, int s, bool for_aggregate, MoveJob &jb) {
+bool make_job(const twist_ctx *ctx, const twist_plan *plan, int l, int t, const void *full_ptr, int s, bool for_aggregate, int n_subs, MoveJob &jb) {
   const twist_model_desc &d = ctx->d;
   const Slot &slot = l >= 0 ? plan->layout.at(l, t) : plan->layout.global[t];
   if (slot.off < 0) return false;
@@ -366,7 +366,11 @@ bool make_job(const twist_ctx *ctx, const twist_plan *plan, int l, int t, const 
   }
   jb.vec = ((int64_t)jb.Q * es) % 16 == 0 && (reinterpret_cast<uintptr_t>(full_ptr) % 16) == 0;
   const int64_t width = (int64_t)(for_aggregate ? jb.n_full : jb.n_sub) * (jb.vec ? jb.Q / VN : jb.Q);
-  if (jb.vec && for_aggregate) {
+  if (jb.vec && jb.rows == 1 && (jb.Q / VN) % 256 == 0 && (!for_aggregate || n_subs <= 8)) {
+    jb.vec = 2;
+    jb.tile_u = for_aggregate ? 2 : 8;
+    jb.tile_rows = 1;
+  } else if (jb.vec && for_aggregate) {
     // the pull keeps up to 8 subnets' vectors per output vector in registers: fewer vectors per thread
     jb.tile_u = jb.rows == 1 ? (width >= 1024 ? 4 : (width >= 512 ? 2 : 1)) : (width >= 512 ? 2 : 1);
     jb.tile_rows = jb.tile_u == 4 ? 1 : (jb.tile_u == 2 ? (jb.rows > 1 ? 2 : 1) : 4);
@@ -395,23 +399,27 @@ twist_status check_full(twist_ctx *ctx, const twist_full_weights *full, const ch
   return TWIST_OK;
 }
 
-// Run `launch` over every layer (and once for the model-level tensors), packing each into one MoveLaunch.
+// Run `launch` over every layer (and once for the model-level tensors).  A layer's row-block jobs go into one
+// launch and its other jobs into a second one when aggregating (which has a lighter kernel for the former).
 template <class F>
 twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int s, bool for_aggregate, MoveLaunch &ml, F launch) {
   const twist_model_desc &d = ctx->d;
   for (int l = -1; l < d.n_layers; ++l) {
-    ml.n_jobs = 0;
-    int blocks = 0;
     const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
-    for (int t = 0; t < nt; ++t) {
-      const void *fp = l < 0 ? full->global_tensors[t] : full->layer_tensors[(size_t)l * TWIST_N_LAYER_TENSORS + t];
-      MoveJob &jb = ml.job[ml.n_jobs];
-      if (!make_job(ctx, plan, l, t, fp, s, for_aggregate, jb)) continue;
-      jb.blk_begin = blocks;
-      blocks += job_blocks(jb);
-      ++ml.n_jobs;
+    for (int pass = 0; pass < (for_aggregate ? 2 : 1); ++pass) {
+      ml.n_jobs = 0;
+      int blocks = 0;
+      for (int t = 0; t < nt; ++t) {
+        const void *fp = l < 0 ? full->global_tensors[t] : full->layer_tensors[(size_t)l * TWIST_N_LAYER_TENSORS + t];
+        MoveJob &jb = ml.job[ml.n_jobs];
+        if (!make_job(ctx, plan, l, t, fp, s, for_aggregate, ml.n_subs, jb)) continue;
+        if (for_aggregate && (jb.vec == 2) != (pass == 0)) continue;
+        jb.blk_begin = blocks;
+        blocks += job_blocks(jb);
+        ++ml.n_jobs;
+      }
+      TW_TRY(launch(ml, blocks));
     }
-    TW_TRY(launch(ml, blocks));
   }
   return TWIST_OK;
 }

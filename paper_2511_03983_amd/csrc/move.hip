@@ -126,13 +126,47 @@ __device__ __forceinline__ void gather_elem(const MoveJob &jb, char *dst_base, i
   }
 }
 
+// Row-block path (jobs whose segments are whole multiples of 256 vectors: blocks of matrix rows).  Every group of
+// 256 consecutive destination vectors lies inside one unit, so the blueprint entry is one scalar load per group
+// instead of a dependent per-lane lookup, and a thread keeps TU independent 16-byte loads in flight.
+template <int ES, int TU>
+__device__ __forceinline__ void gather_rows(const MoveJob &jb, char *dst_base, int lb) {
+  using V = typename VecOf<ES>::vec;
+  constexpr int VN = VecOf<ES>::N;
+  const int qv = jb.Q / VN;
+  const int64_t Ws = (int64_t)jb.n_sub * qv;
+  const V *src = reinterpret_cast<const V *>(jb.full);
+  V *dst = reinterpret_cast<V *>(dst_base + jb.sub_off * ES);
+  const int64_t g0 = (int64_t)lb * (kThreads * TU);
+  V val[TU];
+  int64_t sv[TU];
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const int64_t g = g0 + u * kThreads;  // first vector of the group: uniform over the workgroup
+    sv[u] = -1;
+    if (g < Ws) {
+      const int k = __builtin_amdgcn_readfirstlane((int)(g / qv));
+      const int unit = jb.table ? jb.table[k] : k;
+      sv[u] = (int64_t)unit * qv + (g - (int64_t)k * qv) + threadIdx.x;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < TU; ++u)
+    if (sv[u] >= 0) val[u] = __builtin_nontemporal_load(&src[sv[u]]);
+#pragma unroll
+  for (int u = 0; u < TU; ++u)
+    if (sv[u] >= 0) __builtin_nontemporal_store(val[u], &dst[g0 + u * kThreads + threadIdx.x]);
+}
+
 template <int ES>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const MoveLaunch ml) {
   const int ji = find_job(ml, blockIdx.x);
   const MoveJob &jb = ml.job[ji];
   const int lb = blockIdx.x - jb.blk_begin;
   char *dst_base = const_cast<char *>(ml.sub_base[0]);
-  if (jb.vec) {
+  if (jb.vec == 2) {
+    gather_rows<ES, 8>(jb, dst_base, lb);
+  } else if (jb.vec) {
     if (jb.tile_u == 4) gather_vec<ES, 1, 4>(jb, dst_base, lb);
     else if (jb.tile_u == 2) gather_vec<ES, 2, 2>(jb, dst_base, lb);
     else gather_vec<ES, 4, 1>(jb, dst_base, lb);
@@ -365,6 +399,55 @@ __device__ __forceinline__ void pull_elem(const MoveLaunch &ml, const MoveJob &j
   }
 }
 
+// Row-block path of the pull (see gather_rows): the owners of a group of 256 central vectors are found with
+// scalar loads of the inverse table, and only the subnets that hold the unit are read.
+template <int ES, int TU>
+__device__ __forceinline__ void pull_rows(const MoveLaunch &ml, const MoveJob &jb, int lb) {
+  using V = typename VecOf<ES>::vec;
+  constexpr int VN = VecOf<ES>::N;
+  const int qv = jb.Q / VN;
+  const int64_t Wf = (int64_t)jb.n_full * qv;  // a multiple of 256: a group is entirely inside or outside
+  V *full = reinterpret_cast<V *>(const_cast<void *>(jb.full));
+  const int64_t g0 = (int64_t)lb * (kThreads * TU);
+  V val[TU][kChunk];
+  int n_own[TU];
+  bool own[TU][kChunk];
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const int64_t g = g0 + u * kThreads;
+    n_own[u] = 0;
+    const bool in = g < Wf;
+    const int unit = in ? __builtin_amdgcn_readfirstlane((int)(g / qv)) : 0;
+    const int64_t j = g - (int64_t)unit * qv + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      own[u][i] = false;
+      if (in && i < ml.n_subs) {
+        const int p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+        if (p >= 0) {
+          own[u][i] = true;
+          ++n_own[u];
+          const V *sp = reinterpret_cast<const V *>(ml.sub_base[i] + jb.sub_off * ES);
+          val[u][i] = __builtin_nontemporal_load(&sp[(int64_t)p * qv + j]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    if (n_own[u] == 0) continue;  // no owner: the central values stay
+    Acc<ES> acc;
+    bool first = true;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      if (own[u][i]) {
+        if (first) acc.set(val[u][i]); else acc.add(val[u][i]);
+        first = false;
+      }
+    __builtin_nontemporal_store(acc.mean(n_own[u]), &full[g0 + u * kThreads + threadIdx.x]);
+  }
+}
+
 template <int ES>
 __global__ __launch_bounds__(kThreads) void aggregate_kernel(const MoveLaunch ml) {
   const int ji = find_job(ml, blockIdx.x);
@@ -378,6 +461,14 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const MoveLaunch ml
   } else {
     pull_elem<ES>(ml, jb, lb);
   }
+}
+
+// launches that hold row-block jobs only: far fewer registers than the general kernel, hence more waves in flight
+template <int ES, int TU>
+__global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(const MoveLaunch ml) {
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  pull_rows<ES, TU>(ml, jb, blockIdx.x - jb.blk_begin);
 }
 
 // ------------------------------------------------------------------------------------------- helpers
@@ -406,7 +497,12 @@ twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int tota
 
 twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks) {
   if (total_blocks <= 0) return TWIST_OK;
-  if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  bool rows_only = true;
+  for (int i = 0; i < ml.n_jobs; ++i) rows_only = rows_only && ml.job[i].vec == 2;
+  if (rows_only) {  // the host gives such jobs tile_u = 2
+    if (ctx->esize() == 2) hipLaunchKernelGGL((aggregate_rows_kernel<2, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+    else hipLaunchKernelGGL((aggregate_rows_kernel<4, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  } else if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   else hipLaunchKernelGGL(aggregate_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;

@@ -109,7 +109,8 @@ struct MoveJob {
   int32_t rows, n_full, n_sub, Q;
   int32_t tile_rows, tile_u;  // a workgroup covers tile_rows rows x 256*tile_u vectors (or elements)
   int32_t tiles_per_row;      // ceil(width / (256*tile_u))
-  int32_t vec;                // 1 = 16-byte path usable, 0 = element path
+  int32_t vec;                // 0 = element path, 1 = 16-byte path, 2 = 16-byte row-block path (segments of whole
+                              //     multiples of 256 vectors, one row, at most 8 subnets)
   int32_t blk_begin;          // first workgroup of this job inside the launch
 };
 
