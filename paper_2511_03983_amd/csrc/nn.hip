@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kT) void norm_bwd_dx_kernel(const void *dy, const f
   }
 }
 
-constexpr int kChunkRows = 128;
+constexpr int kChunkRows = 16;
 
 // partial[chunk][0][c] = sum over the chunk's rows of dy*z ; partial[chunk][1][c] = sum of dy
 template <int BF>
@@ -159,13 +159,95 @@ __global__ __launch_bounds__(64) void norm_bwd_dw_kernel(const void *dy, const f
   partial[((int64_t)chunk * 2 + 1) * D + c] = sb;
 }
 
-// out[c] = alpha * sum_k partial[k*stride + c]
+// Fused norm backward for rows of NV * 256 elements: one pass over dy and x yields dx (+= when accumulating), its
+// activation-type copy, and this chunk's partial sums for the gain / bias gradients.  A wave owns a row at a time and
+// a lane the same 4 NV columns of every row (vector v = lane + 64 k holds columns 4v .. 4v+3), so the parameter sums
+// stay in registers across the chunk's rows; the four waves' sums are combined through LDS.
+template <int BF, int RMS, int NV>
+__global__ __launch_bounds__(kT) void norm_bwd_fused_kernel(const void *dy, const float *x, const void *w, const float *stats, float *dx, int accumulate,
+                                                             void *dxb, float *partial, int T) {
+  constexpr int D = NV * 256;
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  __shared__ float red[(RMS ? 1 : 2) * 4 * D];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r0 = blockIdx.x * kChunkRows, r1 = min(r0 + kChunkRows, T);
+  auto load4 = [](const void *p, int64_t vec) -> f4 {
+    if (BF) {
+      const u2 u = static_cast<const u2 *>(p)[vec];
+      return f4{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
+    }
+    return static_cast<const f4 *>(p)[vec];
+  };
+  f4 wv[NV], aw[NV], ab[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    wv[k] = load4(w, lane + 64 * k);
+    aw[k] = f4{0.f, 0.f, 0.f, 0.f};
+    ab[k] = f4{0.f, 0.f, 0.f, 0.f};
+  }
+  for (int r = r0 + wave; r < r1; r += 4) {
+    const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+    const int64_t rv = (int64_t)r * (D / 4);
+    f4 g[NV], z[NV];
+    float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      g[k] = load4(dy, rv + lane + 64 * k);
+      z[k] = (reinterpret_cast<const f4 *>(x)[rv + lane + 64 * k] - mean) * rstd;
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      aw[k] += g[k] * z[k];
+      if (!RMS) ab[k] += g[k];
+      g[k] *= wv[k];  // dz
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { c1 += g[k][e]; c2 += g[k][e] * z[k][e]; }
+    }
+    c1 = RMS ? 0.f : wave_sum(c1) / D;
+    c2 = wave_sum(c2) / D;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      f4 o = rstd * (g[k] - c1 - z[k] * c2);
+      f4 *dp = reinterpret_cast<f4 *>(dx) + rv + lane + 64 * k;
+      if (accumulate) o += *dp;
+      *dp = o;
+      if (dxb) {
+        if (BF) {
+          typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+          typedef float f2 __attribute__((ext_vector_type(2)));
+          const f2 lo = {o[0], o[1]}, hi = {o[2], o[3]};
+          const u2 pk = {__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2))};
+          static_cast<u2 *>(dxb)[rv + lane + 64 * k] = pk;
+        } else {
+          static_cast<f4 *>(dxb)[rv + lane + 64 * k] = o;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    *reinterpret_cast<f4 *>(&red[wave * D + 4 * (lane + 64 * k)]) = aw[k];
+    if (!RMS) *reinterpret_cast<f4 *>(&red[(4 + wave) * D + 4 * (lane + 64 * k)]) = ab[k];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < D; c += kT) {
+    partial[((int64_t)blockIdx.x * 2) * D + c] = red[c] + red[D + c] + red[2 * D + c] + red[3 * D + c];
+    if (!RMS) partial[((int64_t)blockIdx.x * 2 + 1) * D + c] = red[4 * D + c] + red[5 * D + c] + red[6 * D + c] + red[7 * D + c];
+  }
+}
+
+// out[c] = alpha * sum_k partial[k*stride + c].  A workgroup owns 64 columns; its 256 threads are 4 chunk slices x
+// 64 columns, each summing every fourth chunk in ascending order, and the four slices are added in order at the end.
 __global__ __launch_bounds__(kT) void reduce_partial_kernel(const float *partial, int64_t stride, int n_chunks, float alpha, float *out, int n) {
-  const int c = blockIdx.x * kT + threadIdx.x;
-  if (c >= n) return;
+  __shared__ float sh[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), slice = threadIdx.x >> 6;
   float s = 0.f;
-  for (int k = 0; k < n_chunks; ++k) s += partial[(int64_t)k * stride + c];
-  out[c] = alpha * s;
+  if (c < n)
+    for (int k = slice; k < n_chunks; k += 4) s += partial[(int64_t)k * stride + c];
+  sh[slice][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (slice == 0 && c < n) out[c] = alpha * (sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x]);
 }
 
 template <int BF>
@@ -395,13 +477,41 @@ size_t twist_colsum_partial_floats(int T, int n) { return (size_t)n_chunks(T) * 
 
 twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
                             int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D) {
-  // parameter gradients first: they read dy and x, which the dx pass leaves untouched
   const int nc = n_chunks(T);
+  const auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const int nv = D % 256 == 0 ? D / 256 : 0;
+  const bool fused_ok = al16(dy) && al16(x) && al16(w) && al16(dx) && (!dxb || al16(dxb)) && (nv == 1 || nv == 2 || nv == 3 || nv == 4 || nv == 8 || (nv == 16 && rms && bf16));
+  if (fused_ok) {
+#define TW_NORM_FUSED(NV)                                                                                                                              \
+  do {                                                                                                                                                 \
+    if (bf16 && rms) hipLaunchKernelGGL((norm_bwd_fused_kernel<1, 1, NV>), dim3(nc), dim3(kT), 0, ctx->stream, dy, x, w, stats, dx, accumulate, dxb, partial, T);      \
+    else if (bf16) hipLaunchKernelGGL((norm_bwd_fused_kernel<1, 0, NV>), dim3(nc), dim3(kT), 0, ctx->stream, dy, x, w, stats, dx, accumulate, dxb, partial, T);       \
+    else if (rms) hipLaunchKernelGGL((norm_bwd_fused_kernel<0, 1, NV>), dim3(nc), dim3(kT), 0, ctx->stream, dy, x, w, stats, dx, accumulate, dxb, partial, T);        \
+    else hipLaunchKernelGGL((norm_bwd_fused_kernel<0, 0, NV>), dim3(nc), dim3(kT), 0, ctx->stream, dy, x, w, stats, dx, accumulate, dxb, partial, T);                 \
+  } while (0)
+    switch (nv) {
+      case 1: TW_NORM_FUSED(1); break;
+      case 2: TW_NORM_FUSED(2); break;
+      case 3: TW_NORM_FUSED(3); break;
+      case 4: TW_NORM_FUSED(4); break;
+      case 8: TW_NORM_FUSED(8); break;
+      default:
+        hipLaunchKernelGGL((norm_bwd_fused_kernel<1, 1, 16>), dim3(nc), dim3(kT), 0, ctx->stream, dy, x, w, stats, dx, accumulate, dxb, partial, T);
+        break;
+    }
+#undef TW_NORM_FUSED
+    TW_HIP(ctx, hipGetLastError());
+    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+    if (db) hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
+  // general shapes: parameter gradients first (they read dy and x, which the dx pass leaves untouched)
   LAUNCH_BF(norm_bwd_dw_kernel, bf16, dim3((D + 63) / 64, nc), dim3(64), dy, x, stats, partial, T, D);
-  hipLaunchKernelGGL(reduce_partial_kernel, grid1(D), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+  hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
   TW_HIP(ctx, hipGetLastError());
   if (db) {
-    hipLaunchKernelGGL(reduce_partial_kernel, grid1(D), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
+    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
     TW_HIP(ctx, hipGetLastError());
   }
   LAUNCH_BF2(norm_bwd_dx_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), dy, x, w, stats, dx, accumulate, dxb, T, D);
@@ -411,7 +521,7 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
 twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int n) {
   const int nc = n_chunks(T);
   LAUNCH_BF(colsum_kernel, bf16, dim3((n + 63) / 64, nc), dim3(64), src, ld, partial, T, n);
-  hipLaunchKernelGGL(reduce_partial_kernel, grid1(n), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
+  hipLaunchKernelGGL(reduce_partial_kernel, dim3((n + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }
