@@ -199,6 +199,15 @@ TWIST_API twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, t
 TWIST_API twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M, int32_t N, int32_t K, const void *A, int64_t lda,
                                       const void *B, int64_t ldb, void *C, int64_t ldc, int32_t out_f32, float alpha);
 
+/* Kernel-level entry point for tests: causal multi-head attention of Appendix A.1 in isolation, forward and (when
+ * dout is not NULL) backward, on a fused activation buffer qkv [B*N, 3*Hs*d_head] (q | k | v, desc.dtype).
+ * Outputs: o [B*N, Hs*d_head] (desc.dtype), lse [B, Hs, N] fp32 (log-sum-exp of the scaled scores), and dqkv
+ * [B*N, 3*Hs*d_head] from dout [B*N, Hs*d_head].  o32 [B*N, Hs*d_head] fp32 and delta [B, Hs, N] fp32 are
+ * caller-provided scratch (o32 receives the unrounded output of bf16 models).  All device pointers, caller-owned;
+ * work is enqueued on the ctx's stream.  TWIST_ESHAPE if d_head exceeds 256. */
+TWIST_API twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs,
+                                           void *o, float *o32, float *lse, float *delta, void *dqkv);
+
 /* Measurement aid for benchmarks (not part of the method): while enabled, every projection (GEMM) launch on
  * this ctx is bracketed by two HIP events on the ctx's stream.  twist_profile_gemm_read synchronises the
  * stream, returns the number of launches, their summed duration in milliseconds and their summed algorithmic

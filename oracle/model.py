@@ -97,6 +97,30 @@ def rope_apply(x, cos, sin, sign=1.0):
 
 
 # ----------------------------------------------------------------------------- model
+def attention_fwd(qh, kh, vh):
+    """Causal multi-head attention of Appendix A.1 on [B, N, H, d_head] arrays: softmax(Q K^T / sqrt(d_head)) V
+    per head with keys after the query masked out.  Returns (output [B, N, H, d_head], probabilities [B, H, N, N])."""
+    N, dh = qh.shape[1], qh.shape[3]
+    causal = np.triu(np.ones((N, N), dtype=bool), k=1)
+    sc = np.einsum("bnhe,bmhe->bhnm", qh, kh) / math.sqrt(dh)
+    sc = np.where(causal[None, None], -np.inf, sc)
+    sc = sc - sc.max(-1, keepdims=True)
+    p = np.exp(sc)
+    p = p / p.sum(-1, keepdims=True)
+    return np.einsum("bhnm,bmhe->bnhe", p, vh), p
+
+
+def attention_bwd(p, qh, kh, vh, do):
+    """Gradients of attention_fwd's output with respect to q, k, v given d(output) = do (all [B, N, H, d_head])."""
+    dh = qh.shape[3]
+    dv = np.einsum("bhnm,bnhe->bmhe", p, do)
+    dp = np.einsum("bnhe,bmhe->bhnm", do, vh)
+    ds = p * (dp - (dp * p).sum(-1, keepdims=True)) / math.sqrt(dh)
+    dq = np.einsum("bhnm,bmhe->bnhe", ds, kh)
+    dk = np.einsum("bhnm,bnhe->bmhe", ds, qh)
+    return dq, dk, dv
+
+
 def scale_factors(cfg, lw, scale_mode):
     """(c_attn, c_ffn) of one layer, from the subnet's widths."""
     if not scale_mode:
@@ -121,7 +145,6 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         X = np.asarray(inputs, dtype=np.float64)
         B, N, _ = X.shape
     cos, sin = rope_tables(N, dh, cfg.rope_theta) if cfg.rope else (None, None)
-    causal = np.triu(np.ones((N, N), dtype=bool), k=1)
     caches = []
 
     for lw in P["layers"]:
@@ -137,12 +160,8 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         qh, kh, vh = (q("qkv", t).reshape(B, N, Hs, dh) for t in (qh, kh, vh))
         if cfg.rope:
             qh, kh = q("qkv", rope_apply(qh, cos, sin)), q("qkv", rope_apply(kh, cos, sin))
-        sc = np.einsum("bnhe,bmhe->bhnm", qh, kh) / math.sqrt(dh)
-        sc = np.where(causal[None, None], -np.inf, sc)
-        sc = sc - sc.max(-1, keepdims=True)
-        p = np.exp(sc)
-        p = p / p.sum(-1, keepdims=True)
-        o = q("o", np.einsum("bhnm,bmhe->bnhe", p, vh).reshape(B, N, Hs * dh))
+        o, p = attention_fwd(qh, kh, vh)
+        o = q("o", o.reshape(B, N, Hs * dh))
         c.update(q=qh, k=kh, v=vh, p=p, o=o)
         y = o @ lw["wo"].T + lw.get("bo", 0.0)
         X = X + c_a * y
@@ -239,11 +258,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
             g_["bo"] = dyf.sum(0)
         do = q("dact", dy @ lw["wo"]).reshape(B, N, Hs, dh)
         p, qh, kh, vh = c["p"], c["q"], c["k"], c["v"]
-        dv = np.einsum("bhnm,bnhe->bmhe", p, do)
-        dp = np.einsum("bnhe,bmhe->bhnm", do, vh)
-        ds = p * (dp - (dp * p).sum(-1, keepdims=True)) / math.sqrt(dh)
-        dq = np.einsum("bhnm,bmhe->bnhe", ds, kh)
-        dk = np.einsum("bhnm,bnhe->bmhe", ds, qh)
+        dq, dk, dv = attention_bwd(p, qh, kh, vh, do)
         if cfg.rope:
             dq, dk = q("dact", dq), q("dact", dk)      # rounding point only; identity by default
             dq, dk = rope_apply(dq, cos, sin, -1.0), rope_apply(dk, cos, sin, -1.0)

@@ -81,6 +81,7 @@ _SIGS = {
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
+    "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
     "twist_set_overlap": ([_vp, _i32], _i32),
     "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
@@ -170,6 +171,19 @@ class Context:
         _check(lib.twist_gemm_raw(self.h, layout, M, N, K, _vp(A.data_ptr()), A.stride(0), _vp(B.data_ptr()), B.stride(0),
                                   _vp(out.data_ptr()), out.stride(0), int(out.dtype == torch.float32 and self.torch_dtype != torch.float32
                                                                           or out.dtype == torch.float32), alpha), self.h)
+
+    def twist_attention_raw(self, qkv: torch.Tensor, dout, B: int, N: int, Hs: int):
+        """Causal attention alone: returns (o, lse, dqkv or None) for qkv [B*N, 3*Hs*d_head] and dout [B*N, Hs*d_head] or None."""
+        T, HD = B * N, qkv.shape[1] // 3
+        o = torch.empty((T, HD), dtype=qkv.dtype, device=qkv.device)
+        o32 = torch.empty((T, HD), dtype=torch.float32, device=qkv.device)
+        lse = torch.empty((B, Hs, N), dtype=torch.float32, device=qkv.device)
+        delta = torch.empty_like(lse)
+        dqkv = torch.empty_like(qkv) if dout is not None else None
+        _check(lib.twist_attention_raw(self.h, _vp(qkv.data_ptr()), _vp(dout.data_ptr()) if dout is not None else None, B, N, Hs,
+                                       _vp(o.data_ptr()), _vp(o32.data_ptr()), _vp(lse.data_ptr()), _vp(delta.data_ptr()),
+                                       _vp(dqkv.data_ptr()) if dqkv is not None else None), self.h)
+        return o, lse, dqkv
 
     def twist_set_overlap(self, enable: bool) -> None:
         _check(lib.twist_set_overlap(self.h, int(enable)), self.h)

@@ -207,3 +207,16 @@ twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, cons
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }
+
+extern "C" twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs, void *o, float *o32,
+                                            float *lse, float *delta, void *dqkv) {
+  if (!ctx || !qkv || !o || !o32 || !lse) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: null argument");
+  if (B < 1 || N < 1 || Hs < 1) TW_FAIL(ctx, TWIST_ESHAPE, "twist_attention_raw: empty shape");
+  const int bf = ctx->d.dtype == TWIST_BF16;
+  TW_TRY(twist_attention_fwd(ctx, bf, qkv, o, o32, lse, B, N, Hs, ctx->d.d_head));
+  if (dout) {
+    if (!delta || !dqkv) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: backward needs delta and dqkv");
+    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head));
+  }
+  return TWIST_OK;
+}

@@ -3,6 +3,8 @@
 //    operands staged through LDS in their memory orientation; operands whose contraction index is the slow
 //    axis in memory are read back with the transposing LDS load.
 //  - anything else (fp32 models, unaligned shapes): a plain tiled FMA kernel with arbitrary strides.
+#include <algorithm>
+
 #include "nn.h"
 
 namespace {
@@ -361,17 +363,25 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
   constexpr int SMEM = NST * STG > 8 * EPI_WAVE ? NST * STG : 8 * EPI_WAVE;
   __shared__ __attribute__((aligned(1024))) char smem[SMEM];
   const int nb = tiles_m * tiles_n;
-  int bid = blockIdx.x;
-  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;  // each XCD (own L2) gets a contiguous range of tiles
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wpos = wave & 3, half = wave >> 2;  // waves w and w+4 share a SIMD and sit in different groups
+  const int wm = (wpos >> 1) * 128 + half * 64, wn = (wpos & 1) * 128;
+  Frags<AKM, TM> fa;
+  Frags<BKM, TN> fb;
+  fa.init(wm, lane);
+  fb.init(wn, lane);
+  // Persistent workgroups: each walks the tiles vid, vid + gridDim.x, ...; the stores of one tile drain while the
+  // next tile's loads are already under way.  Tile numbers are dealt so that each of the 8 XCDs (own L2; workgroup
+  // b runs on XCD b % 8) works on a contiguous range of tiles.
+  for (int vid = blockIdx.x; vid < nb; vid += gridDim.x) {
+  int bid = vid;
+  if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
   constexpr int GROUP = 8;
   const int per_group = GROUP * tiles_n;
   const int grp = bid / per_group, first_m = grp * GROUP;
   const int gsize = min(GROUP, tiles_m - first_m);
   const int tile_m = first_m + (bid % per_group) % gsize, tile_n = (bid % per_group) / gsize;
   const int m0 = tile_m * 256, n0 = tile_n * 256;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int wpos = wave & 3, half = wave >> 2;  // waves w and w+4 share a SIMD and sit in different groups
-  const int wm = (wpos >> 1) * 128 + half * 64, wn = (wpos & 1) * 128;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -385,10 +395,6 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
   Loader<BKM> lb;
   la.init(AKM ? A + (int64_t)m0 * lda : A + m0, lda, M - m0, K, wave, lane);
   lb.init(BKM ? B + (int64_t)n0 * ldb : B + n0, ldb, N - n0, K, wave, lane);
-  Frags<AKM, TM> fa;
-  Frags<BKM, TN> fb;
-  fa.init(wm, lane);
-  fb.init(wn, lane);
 
   const int nsub = (K + SK - 1) / SK;
 #pragma unroll
@@ -487,6 +493,9 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
       }
     }
   }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's staged results are in registers
+  __builtin_amdgcn_s_barrier();        // everybody's are: the next tile's loads may overwrite the staging area
+  }
 }
 
 }  // namespace pp
@@ -500,7 +509,8 @@ void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t
   static const bool old_impl = getenv("TWIST_GEMM_OLD") != nullptr;  // test knob: the single-phase 256x256 kernel
   if (use_big && !old_impl) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
-    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+    static const int persist = getenv("TWIST_GEMM_PERSIST") ? atoi(getenv("TWIST_GEMM_PERSIST")) : 256;
+    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(std::min(tm * tn, persist)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
   } else if (use_big) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
     hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 256, 256, 4, 2>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
