@@ -17,6 +17,8 @@
 // convex combination of the value rows; the dQ kernel forms delta from that fp32 output in its prologue.  With
 // both in place a component common to all value rows (a large value bias) cancels exactly in p (dp - delta),
 // which it does not when delta is taken from the bf16-rounded output.
+#include <type_traits>
+
 #include "nn.h"
 
 namespace {
@@ -122,9 +124,9 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LDK + ks * 16 + g * 8), qf[ks], s[mt]);
+      for (int ks = 0; ks < KS; ++ks) s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LDK + ks * 16 + g * 8), qf[ks], s[mt]);
     const bool diag = kt * 64 + 63 > q0;
     float mx = -INFINITY;
     if (diag) {
@@ -242,9 +244,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+      for (int ks = 0; ks < KS; ++ks) {
         s[mt] = MFMA(lds_frag(Ks + (mt * 32 + c) * LD + ks * 16 + g * 8), qf[ks], s[mt]);
         dp[mt] = MFMA(lds_frag(Vs + (mt * 32 + c) * LD + ks * 16 + g * 8), gf[ks], dp[mt]);
       }
@@ -327,9 +329,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
+      for (int ks = 0; ks < KS; ++ks) {
         s[mt] = MFMA(lds_frag(Qs + (mt * 32 + c) * LD + ks * 16 + g * 8), kf[ks], s[mt]);
         dp[mt] = MFMA(lds_frag(Gs + (mt * 32 + c) * LD + ks * 16 + g * 8), vf[ks], dp[mt]);
       }
@@ -368,6 +370,393 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
     }
 }
 
+// =========================================================================================== d_head = 128, pipelined
+// Same decomposition, but the 64 x 128 key / value (or query / dO) tiles of step t+1 travel from global memory
+// straight into LDS (buffer_load_dwordx4 ... lds, lane l of a wave writes 16 bytes at base + 16 l) while step t is
+// computed: two stages of two 16 KB tiles, one barrier per step.  The fixed write pattern leaves no room for row
+// padding; bank conflicts are avoided by storing chunk c (16 bytes) of row r at position c ^ swz(r),
+// swz(r) = 4 (r & 3) + ((r >> 2) & 3), which serves both read patterns: 16 consecutive rows of one chunk column
+// (plain 16-byte fragment reads) and 4 consecutive rows of two adjacent chunks (transposing reads).
+namespace dl {
+
+constexpr int DH = 128, KS = 8, MT = 4;
+constexpr int TILE_B = 64 * DH * 2;    // one staged tile
+constexpr int STAGE_B = 2 * TILE_B;    // K and V (or Q and dO)
+typedef __attribute__((address_space(3))) void *lds_void;
+
+__device__ __forceinline__ int swz(int r) { return 4 * (r & 3) + ((r >> 2) & 3); }
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+// Per-lane byte offsets (within a tile) of the two kinds of fragment reads.
+struct ReadOffsets {
+  uint32_t fo[KS];          // plain fragment of k-step ks for tile row (lane & 31); add 8192 per 32 rows
+  uint32_t ta[MT], tb[MT];  // transposing reads of head-dim block i: contraction rows +0..3 and +8..11; add 256 per row
+  __device__ __forceinline__ void init(int lane) {
+    const int c = lane & 31, g = lane >> 5, s16 = lane & 15, rho = (s16 >> 2) & 3, dlt = (s16 & 3) >> 1, hi = (lane >> 4) & 1;
+    const int x = swz(c);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fo[ks] = (uint32_t)(c * 256 + (((2 * ks + g) ^ x) << 4));
+    const int within = (s16 & 1) * 8;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      ta[i] = (uint32_t)((4 * g + rho) * 256 + within + (((2 * hi + dlt) ^ g) << 4) + ((i ^ rho) << 6));
+      tb[i] = (uint32_t)((4 * g + rho + 8) * 256 + within + (((2 * hi + dlt) ^ (g + 2)) << 4) + ((i ^ rho) << 6));
+    }
+  }
+};
+
+__device__ __forceinline__ bf16x8 frag(const char *tile, uint32_t off) { return *reinterpret_cast<const bf16x8 *>(tile + off); }
+__device__ __forceinline__ bf16x8 frag_tr(const char *rows, uint32_t a, uint32_t b) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(rows + a));
+  s16x4 y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(rows + b));
+  s16x8 v = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Each of the 4 waves brings in 4 of the 16 one-KB pieces (4 rows each) of a tile.
+struct TileLoader {
+  uint32_t off[4];  // byte offset of this lane's chunk within tile 0, from the buffer base
+  __device__ __forceinline__ void init(int64_t ld_elems, uint32_t col_byte0, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 4 * (wave + 4 * i) + (lane >> 4), chunk = (lane & 15) ^ swz(row);
+      off[i] = (uint32_t)(row * ld_elems * 2) + col_byte0 + chunk * 16;
+    }
+  }
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, char *dst, uint32_t tile_byte0, int wave) const {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void)(dst + (wave + 4 * i) * 1024), 16, off[i] + tile_byte0, 0, 0, 0);
+  }
+};
+
+#define DL_WAIT_VM0 __builtin_amdgcn_s_waitcnt(0x0f70)
+
+__global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
+  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+  const int nqb = N / 128, nbh = gridDim.x / nqb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - rank / nbh;
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *batch = qkv + (int64_t)b * N * ld;
+  const uint16_t *qp = batch + (int64_t)h * DH;
+  const int q0 = qb * 128 + wave * 32, q = q0 + c;
+  const float sc = scale * kLog2e;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(batch, (uint32_t)(N * ld * 2));
+  const uint32_t tstep = (uint32_t)(64 * ld * 2);
+  TileLoader lk, lv;
+  lk.init(ld, (uint32_t)((HD + h * DH) * 2), wave, lane);
+  lv.init(ld, (uint32_t)((2 * HD + h * DH) * 2), wave, lane);
+  ReadOffsets ro;
+  ro.init(lane);
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)q * ld + ks * 16 + g * 8);
+  f32x16 oacc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int n_tiles = (qb + 1) * 2;
+  lk.issue(rs, smem, 0, wave);
+  lv.issue(rs, smem + TILE_B, 0, wave);
+  auto step = [&](int kt, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    DL_WAIT_VM0;                    // this wave's pieces of tile kt have landed
+    __builtin_amdgcn_s_barrier();   // everybody's have, and everybody is done with the other stage
+    if (kt + 1 < n_tiles) {
+      lk.issue(rs, smem + (ST ^ 1) * STAGE_B, (uint32_t)(kt + 1) * tstep, wave);
+      lv.issue(rs, smem + (ST ^ 1) * STAGE_B + TILE_B, (uint32_t)(kt + 1) * tstep, wave);
+    }
+    if (kt * 64 > q0 + 31) return;  // whole tile is in this wave's future
+    const char *Kt = smem + ST * STAGE_B, *Vt = Kt + TILE_B;
+    f32x16 s[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) s[mt] = MFMA(frag(Kt + mt * 8192, ro.fo[ks]), qf[ks], s[mt]);
+    }
+    if (kt * 64 + 63 > q0) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (kv > q) s[mt][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
+    const float alpha = exp2f(m - mn);
+    uint32_t pk[2][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const uint32_t u = pack2(exp2f(fmaf(s[mt][r], sc, -mn)), exp2f(fmaf(s[mt][r + 1], sc, -mn)));
+        pk[mt][r >> 1] = u;
+        sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
+      }
+    l = l * alpha + sum;
+    m = mn;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const u32x4 pu = {pk[mt][4 * t], pk[mt][4 * t + 1], pk[mt][4 * t + 2], pk[mt][4 * t + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) oacc[i] = MFMA(frag_tr(Vt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), pf, oacc[i]);
+      }
+  };
+  for (int kt = 0; kt < n_tiles; kt += 2) {
+    step(kt, std::integral_constant<int, 0>());
+    step(kt + 1, std::integral_constant<int, 1>());  // n_tiles is even
+  }
+  l += __shfl_xor(l, 32, 64);
+  const float inv = 1.f / l;
+  uint16_t *op = o + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 w = {pack2(oacc[i][4 * j] * inv, oacc[i][4 * j + 1] * inv), pack2(oacc[i][4 * j + 2] * inv, oacc[i][4 * j + 3] * inv)};
+      *reinterpret_cast<u32x2 *>(op + i * 32 + 8 * j + 4 * g) = w;
+      if (o32) {
+        const f32x4 w4 = {oacc[i][4 * j] * inv, oacc[i][4 * j + 1] * inv, oacc[i][4 * j + 2] * inv, oacc[i][4 * j + 3] * inv};
+        *reinterpret_cast<f32x4 *>(o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH + i * 32 + 8 * j + 4 * g) = w4;
+      }
+    }
+  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
+}
+
+__global__ __launch_bounds__(256) void flash_bwd_dq_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
+                                                              uint16_t *dqkv, int N, int Hs, float scale) {
+  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+  const int nqb = N / 128, nbh = gridDim.x / nqb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - rank / nbh;
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *batch = qkv + (int64_t)b * N * ld;
+  const uint16_t *qp = batch + (int64_t)h * DH;
+  const int q0 = qb * 128 + wave * 32, q = q0 + c;
+  const float sc = scale * kLog2e;
+  const float L2 = lse[((int64_t)b * Hs + h) * N + q] * kLog2e;
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(batch, (uint32_t)(N * ld * 2));
+  const uint32_t tstep = (uint32_t)(64 * ld * 2);
+  TileLoader lk, lv;
+  lk.init(ld, (uint32_t)((HD + h * DH) * 2), wave, lane);
+  lv.init(ld, (uint32_t)((2 * HD + h * DH) * 2), wave, lane);
+  ReadOffsets ro;
+  ro.init(lane);
+  const int n_tiles = (qb + 1) * 2;
+  lk.issue(rs, smem, 0, wave);
+  lv.issue(rs, smem + TILE_B, 0, wave);
+
+  bf16x8 qf[KS], gf[KS];
+  const uint16_t *gp = dout + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+  const float *op32 = o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
+  float dl = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + (int64_t)q * ld + ks * 16 + g * 8);
+    gf[ks] = *reinterpret_cast<const bf16x8 *>(gp + ks * 16 + g * 8);
+    const f32x4 oa = *reinterpret_cast<const f32x4 *>(op32 + ks * 16 + g * 8), ob = *reinterpret_cast<const f32x4 *>(op32 + ks * 16 + g * 8 + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dl += (float)gf[ks][e] * oa[e] + (float)gf[ks][e + 4] * ob[e];
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  if (g == 0) delta[((int64_t)b * Hs + h) * N + q] = dl;
+  f32x16 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  auto step = [&](int kt, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    DL_WAIT_VM0;
+    __builtin_amdgcn_s_barrier();
+    if (kt + 1 < n_tiles) {
+      lk.issue(rs, smem + (ST ^ 1) * STAGE_B, (uint32_t)(kt + 1) * tstep, wave);
+      lv.issue(rs, smem + (ST ^ 1) * STAGE_B + TILE_B, (uint32_t)(kt + 1) * tstep, wave);
+    }
+    if (kt * 64 > q0 + 31) return;
+    const char *Kt = smem + ST * STAGE_B, *Vt = Kt + TILE_B;
+    const bool diag = kt * 64 + 63 > q0;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s = MFMA(frag(Kt + mt * 8192, ro.fo[ks]), qf[ks], s);
+        dp = MFMA(frag(Vt + mt * 8192, ro.fo[ks]), gf[ks], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        float p = exp2f(fmaf(s[r], sc, -L2));
+        if (diag && kv > q) p = 0.f;
+        s[r] = p * (dp[r] - dl) * scale;
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 df = pack8(s, 8 * t);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) acc[i] = MFMA(frag_tr(Kt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), df, acc[i]);
+      }
+    }
+  };
+  for (int kt = 0; kt < n_tiles; kt += 2) {
+    step(kt, std::integral_constant<int, 0>());
+    step(kt + 1, std::integral_constant<int, 1>());
+  }
+  uint16_t *op = dqkv + ((int64_t)b * N + q) * ld + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 w = {pack2(acc[i][4 * j], acc[i][4 * j + 1]), pack2(acc[i][4 * j + 2], acc[i][4 * j + 3])};
+      *reinterpret_cast<u32x2 *>(op + i * 32 + 8 * j + 4 * g) = w;
+    }
+}
+
+__global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
+                                                               uint16_t *dqkv, int N, int Hs, float scale) {
+  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 2 * 512];  // + per stage: 64 log-sum-exps, 64 deltas
+  const int nkb = N / 128, nbh = gridDim.x / nkb;
+  const int rank = snake_rank(blockIdx.x, gridDim.x);
+  const int kb = rank / nbh;
+  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
+  const uint16_t *batch = qkv + (int64_t)b * N * ld;
+  const uint16_t *qp = batch + (int64_t)h * DH;
+  const uint16_t *gbatch = dout + (int64_t)b * N * HD;
+  const int k0 = kb * 128 + wave * 32, kv = k0 + c;
+  const float sc = scale * kLog2e;
+  const float *lse_b = lse + ((int64_t)b * Hs + h) * N, *del_b = delta + ((int64_t)b * Hs + h) * N;
+  const __amdgpu_buffer_rsrc_t rq = make_rsrc(batch, (uint32_t)(N * ld * 2)), rg = make_rsrc(gbatch, (uint32_t)(N * HD * 2));
+  const __amdgpu_buffer_rsrc_t rl = make_rsrc(lse_b, (uint32_t)(N * 4)), rd = make_rsrc(del_b, (uint32_t)(N * 4));
+  const uint32_t qstep = (uint32_t)(64 * ld * 2), gstep = (uint32_t)(64 * HD * 2);
+  TileLoader lq, lg;
+  lq.init(ld, (uint32_t)(h * DH * 2), wave, lane);
+  lg.init(HD, (uint32_t)(h * DH * 2), wave, lane);
+  ReadOffsets ro;
+  ro.init(lane);
+  const int qt0 = kb * 2, n_q = N / 64;
+  auto issue = [&](int qt, int st) {
+    lq.issue(rq, smem + st * STAGE_B, (uint32_t)qt * qstep, wave);
+    lg.issue(rg, smem + st * STAGE_B + TILE_B, (uint32_t)qt * gstep, wave);
+    // the tile's 64 log-sum-exps and deltas: one 4-byte-per-lane load each, by waves 0 and 1
+    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rl, (lds_void)(smem + 2 * STAGE_B + st * 512), 4, (uint32_t)((qt * 64 + lane) * 4), 0, 0, 0);
+    if (wave == 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (lds_void)(smem + 2 * STAGE_B + st * 512 + 256), 4, (uint32_t)((qt * 64 + lane) * 4), 0, 0, 0);
+  };
+  issue(qt0, 0);
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8 *>(qp + HD + (int64_t)kv * ld + ks * 16 + g * 8);
+    vf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 2 * HD + (int64_t)kv * ld + ks * 16 + g * 8);
+  }
+  f32x16 dk[MT], dv[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+
+  auto step = [&](int qt, auto stage_c) {
+    constexpr int ST = decltype(stage_c)::value;
+    DL_WAIT_VM0;
+    __builtin_amdgcn_s_barrier();
+    if (qt + 1 < n_q) issue(qt + 1, ST ^ 1);
+    if (qt * 64 + 63 < k0) return;  // every query of the tile precedes this wave's keys
+    const char *Qt = smem + ST * STAGE_B, *Gt = Qt + TILE_B;
+    const float *Ls = reinterpret_cast<const float *>(smem + 2 * STAGE_B + ST * 512), *Ds = Ls + 64;
+    const bool diag = qt * 64 < k0 + 31;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s = MFMA(frag(Qt + mt * 8192, ro.fo[ks]), kf[ks], s);
+        dp = MFMA(frag(Gt + mt * 8192, ro.fo[ks]), vf[ks], dp);
+      }
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int qrow = mt * 32 + 8 * r4 + 4 * g;  // first of 4 consecutive query rows inside the tile
+        const f32x4 L4 = *reinterpret_cast<const f32x4 *>(Ls + qrow), D4 = *reinterpret_cast<const f32x4 *>(Ds + qrow);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * r4 + e;
+          float p = exp2f(fmaf(s[r], sc, -L4[e] * kLog2e));
+          if (diag && qt * 64 + qrow + e < kv) p = 0.f;
+          dp[r] = p * (dp[r] - D4[e]) * scale;  // dS
+          s[r] = p;
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pf = pack8(s, 8 * t), df = pack8(dp, 8 * t);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          dv[i] = MFMA(frag_tr(Gt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), pf, dv[i]);
+          dk[i] = MFMA(frag_tr(Qt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), df, dk[i]);
+        }
+      }
+    }
+  };
+  for (int qt = qt0; qt < n_q; qt += 2) {  // qt0 and n_q are even
+    step(qt, std::integral_constant<int, 0>());
+    step(qt + 1, std::integral_constant<int, 1>());
+  }
+  uint16_t *op = dqkv + ((int64_t)b * N + kv) * ld + (int64_t)h * DH;
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 wk = {pack2(dk[i][4 * j], dk[i][4 * j + 1]), pack2(dk[i][4 * j + 2], dk[i][4 * j + 3])};
+      u32x2 wv = {pack2(dv[i][4 * j], dv[i][4 * j + 1]), pack2(dv[i][4 * j + 2], dv[i][4 * j + 3])};
+      *reinterpret_cast<u32x2 *>(op + HD + i * 32 + 8 * j + 4 * g) = wk;
+      *reinterpret_cast<u32x2 *>(op + 2 * HD + i * 32 + 8 * j + 4 * g) = wv;
+    }
+}
+
+}  // namespace dl
+
+// the pipelined kernels address a whole batch element through one 32-bit buffer range
+bool dl_ok(int B, int N, int Hs, int dh) {
+  static const bool off = getenv("TWIST_FLASH_NO_DL") != nullptr;
+  (void)B;
+  return !off && (int64_t)N * 3 * Hs * dh * 2 < (1ll << 31);
+}
+
 bool shape_ok(const void *a, const void *b, int N, int Hs, int dh) {
   (void)Hs;
   return (dh == 64 || dh == 128) && N % 128 == 0 && (reinterpret_cast<uintptr_t>(a) % 16) == 0 && (reinterpret_cast<uintptr_t>(b) % 16) == 0;
@@ -382,7 +771,8 @@ twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, 
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv);
-  if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
+  if (dh == 128 && dl_ok(B, N, Hs, dh)) hipLaunchKernelGGL(dl::flash_fwd_dl_kernel, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
+  else if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
   else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
   TW_HIP(ctx, hipGetLastError());
   *done = true;
@@ -398,7 +788,10 @@ twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const flo
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv), *gout = static_cast<const uint16_t *>(dout);
   uint16_t *dx = static_cast<uint16_t *>(dqkv);
-  if (dh == 128) {
+  if (dh == 128 && dl_ok(B, N, Hs, dh)) {
+    hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+  } else if (dh == 128) {
     hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
   } else {

@@ -1,0 +1,64 @@
+"""Condense rocprofv3 output of a run of this library into the short text summaries kept under profiles/.
+
+    python -m paper_2511_03983_amd.profile_summary stats <x_kernel_stats.csv> <out.txt> "<command that was profiled>"
+    python -m paper_2511_03983_amd.profile_summary pmc   <x_counter_collection.csv> <out.txt> "<command that was profiled>"
+
+`stats` takes the per-kernel table of `rocprofv3 --kernel-trace --stats --output-format csv`; `pmc` takes the
+per-dispatch counter table of `rocprofv3 --pmc <counter> --output-format csv`, sums the rows of each dispatch and
+averages per (kernel, grid size).  Kernel names are shortened; rows of other libraries' kernels are kept but
+marked.  FETCH_SIZE / WRITE_SIZE are reported by the tool in KiB per dispatch.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import re
+import sys
+
+
+def short(name: str) -> str:
+    name = re.sub(r"\(anonymous namespace\)::", "", name)
+    name = re.sub(r"^void ", "", name)
+    return ("other: " + name[:64]) if name.startswith("at::") or name.startswith("__amd") else name.split("(")[0][:76]
+
+
+def stats(src: str, out: str, cmd: str) -> None:
+    rows = list(csv.DictReader(open(src, newline="")))
+    with open(out, "w") as f:
+        f.write("# rocprofv3 --kernel-trace --stats summary (durations in microseconds)\n# command: %s\n" % cmd)
+        f.write("# 'other:' rows are the benchmark's own weight generation / perturbation kernels, outside the timed regions\n")
+        f.write(f"{'kernel':78s} {'calls':>7s} {'total_us':>12s} {'avg_us':>10s} {'%':>6s}\n")
+        for r in rows:
+            pct = float(r["Percentage"])
+            if pct < 0.005:
+                continue
+            f.write(f"{short(r['Name']):78s} {int(r['Calls']):7d} {float(r['TotalDurationNs']) / 1e3:12.1f} "
+                    f"{float(r['AverageNs']) / 1e3:10.2f} {pct:6.2f}\n")
+
+
+def pmc(src: str, out: str, cmd: str) -> None:
+    disp = collections.OrderedDict()
+    with open(src, newline="") as f:
+        for r in csv.DictReader(f):
+            key = (r["Dispatch_Id"], r["Counter_Name"])
+            if key not in disp:
+                disp[key] = [short(r["Kernel_Name"]), r.get("Grid_Size", ""), 0.0]
+            disp[key][2] += float(r["Counter_Value"])
+    agg = collections.defaultdict(lambda: [0, 0.0])
+    for (_, cname), (kn, grid, val) in disp.items():
+        a = agg[(kn, grid, cname)]
+        a[0] += 1
+        a[1] += val
+    with open(out, "w") as f:
+        f.write("# rocprofv3 --pmc summary: average counter value per dispatch, by kernel and grid size (threads)\n# command: %s\n" % cmd)
+        f.write(f"{'kernel':78s} {'grid':>10s} {'counter':>12s} {'dispatches':>10s} {'avg_per_dispatch':>18s}\n")
+        for (kn, grid, cname), (n, tot) in sorted(agg.items(), key=lambda x: -x[1][1]):
+            if kn.startswith("other:") and "copyBuffer" not in kn:
+                continue
+            f.write(f"{kn:78s} {grid:>10s} {cname:>12s} {n:10d} {tot / n:18.1f}\n")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) != 5 or sys.argv[1] not in ("stats", "pmc"):
+        sys.exit(__doc__)
+    (stats if sys.argv[1] == "stats" else pmc)(sys.argv[2], sys.argv[3], sys.argv[4])
