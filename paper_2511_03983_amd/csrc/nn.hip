@@ -417,6 +417,125 @@ __global__ __launch_bounds__(kT) void zero_f32_kernel(float *p, int64_t n) {
   if (i < n) p[i] = 0.f;
 }
 
+// ------------------------------------------------------------------------------------------- 16-byte paths (bf16)
+// Eight bf16 values per thread and access, used when rows are multiples of 8 elements and bases 16-byte aligned.
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+struct F8 { float v[8]; };
+__device__ __forceinline__ F8 unpack8(const u32x4v &u) {
+  F8 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { r.v[2 * i] = __uint_as_float(u[i] << 16); r.v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u); }
+  return r;
+}
+__device__ __forceinline__ u32x4v pack8(const F8 &f) {
+  typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  u32x4v u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f2 p = {f.v[2 * i], f.v[2 * i + 1]};
+    u[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, b2));  // round to nearest even
+  }
+  return u;
+}
+
+// a = silu(g) * u on [T, 2F] (gate | up) -> [T, F]; i8 runs over T * F/8
+__global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u32x4v *a, int F8n, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const int64_t t = i / F8n;
+  const int c = (int)(i - t * F8n);
+  const F8 g = unpack8(gu[t * 2 * F8n + c]), u = unpack8(gu[t * 2 * F8n + F8n + c]);
+  F8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.v[e] = g.v[e] * sigmoidf(g.v[e]) * u.v[e];
+  a[i] = pack8(o);
+}
+
+__global__ __launch_bounds__(kT) void swiglu_bwd_vec_kernel(const u32x4v *gu, const u32x4v *da, u32x4v *dgu, int F8n, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const int64_t t = i / F8n;
+  const int c = (int)(i - t * F8n);
+  const F8 g = unpack8(gu[t * 2 * F8n + c]), u = unpack8(gu[t * 2 * F8n + F8n + c]), d = unpack8(da[i]);
+  F8 dg, du;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float sg = sigmoidf(g.v[e]);
+    du.v[e] = d.v[e] * g.v[e] * sg;
+    dg.v[e] = d.v[e] * u.v[e] * (sg + g.v[e] * sg * (1.f - sg));
+  }
+  dgu[t * 2 * F8n + c] = pack8(dg);
+  dgu[t * 2 * F8n + F8n + c] = pack8(du);
+}
+
+// rotation of the q and k heads of a fused [T, 3 Hs dh] buffer; i runs over T * 2Hs * (dh/16): 8 pairs per thread
+__global__ __launch_bounds__(kT) void rope_vec_kernel(u32x4v *qkv, const float *tab, int N, int Hs, int dh, float sign, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const int half = dh / 2, h8 = half / 8;
+  const int f8 = (int)(i % h8);
+  const int64_t r = i / h8;
+  const int head = (int)(r % (2 * Hs));
+  const int64_t t = r / (2 * Hs);
+  const int pos = (int)(t % N);
+  const int64_t base = (t * (3 * (int64_t)Hs * dh) + (int64_t)head * dh) / 8 + f8;
+  const F8 a = unpack8(qkv[base]), b = unpack8(qkv[base + h8]);
+  const f32x4v *cs = reinterpret_cast<const f32x4v *>(tab + 2 * ((int64_t)pos * half + 8 * f8));  // (cos, sin) pairs
+  F8 oa, ob;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const f32x4v w = cs[e];
+    oa.v[2 * e] = a.v[2 * e] * w[0] - b.v[2 * e] * (sign * w[1]);
+    ob.v[2 * e] = b.v[2 * e] * w[0] + a.v[2 * e] * (sign * w[1]);
+    oa.v[2 * e + 1] = a.v[2 * e + 1] * w[2] - b.v[2 * e + 1] * (sign * w[3]);
+    ob.v[2 * e + 1] = b.v[2 * e + 1] * w[2] + a.v[2 * e + 1] * (sign * w[3]);
+  }
+  qkv[base] = pack8(oa);
+  qkv[base + h8] = pack8(ob);
+}
+
+// norm forward for bf16 outputs and rows of NV * 256 elements: a wave per row, the row held in registers
+template <int RMS, int NV>
+__global__ __launch_bounds__(kT) void norm_fwd_vec_kernel(const float *x, const void *w, const void *b, void *y, float *stats, int T, float eps) {
+  constexpr int D = NV * 256;
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const int64_t rv = (int64_t)row * (D / 4);
+  auto load4b = [](const void *p, int64_t vec) -> f32x4v {
+    const u2 u = static_cast<const u2 *>(p)[vec];
+    return f32x4v{__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u)};
+  };
+  f32x4v xv[NV];
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    xv[k] = reinterpret_cast<const f32x4v *>(x)[rv + lane + 64 * k];
+    s += xv[k][0] + xv[k][1] + xv[k][2] + xv[k][3];
+  }
+  const float mean = RMS ? 0.f : wave_sum(s) / D;
+  float s2 = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    xv[k] -= mean;
+    s2 += xv[k][0] * xv[k][0] + xv[k][1] * xv[k][1] + xv[k][2] * xv[k][2] + xv[k][3] * xv[k][3];
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(s2) / D + eps);
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    f32x4v o = xv[k] * rstd * load4b(w, lane + 64 * k);
+    if (b) o += load4b(b, lane + 64 * k);
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 lo = {o[0], o[1]}, hi = {o[2], o[3]};
+    const u2 pk = {__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2)), __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2))};
+    static_cast<u2 *>(y)[rv + lane + 64 * k] = pk;
+  }
+  if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+}
+
 inline dim3 grid1(int64_t n) { return dim3((unsigned)((n + kT - 1) / kT)); }
 
 }  // namespace
@@ -466,7 +585,28 @@ twist_status twist_cast_in(twist_ctx *ctx, int bf16, const void *src, float *dst
   return TWIST_OK;
 }
 
+static bool al16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 twist_status twist_norm_fwd(twist_ctx *ctx, int bf16, int rms, const float *x, const void *w, const void *b, void *y, float *stats, int T, int D, float eps) {
+  const int nv = D % 256 == 0 ? D / 256 : 0;
+  if (bf16 && al16(x) && al16(w) && al16(y) && (!b || al16(b)) && (nv == 1 || nv == 2 || nv == 3 || nv == 4 || nv == 8 || nv == 16)) {
+#define TW_NORM_FWD(NV)                                                                                                                          \
+  do {                                                                                                                                           \
+    if (rms) hipLaunchKernelGGL((norm_fwd_vec_kernel<1, NV>), dim3((T + 3) / 4), dim3(kT), 0, ctx->stream, x, w, b, y, stats, T, eps);           \
+    else hipLaunchKernelGGL((norm_fwd_vec_kernel<0, NV>), dim3((T + 3) / 4), dim3(kT), 0, ctx->stream, x, w, b, y, stats, T, eps);              \
+  } while (0)
+    switch (nv) {
+      case 1: TW_NORM_FWD(1); break;
+      case 2: TW_NORM_FWD(2); break;
+      case 3: TW_NORM_FWD(3); break;
+      case 4: TW_NORM_FWD(4); break;
+      case 8: TW_NORM_FWD(8); break;
+      default: TW_NORM_FWD(16); break;
+    }
+#undef TW_NORM_FWD
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   LAUNCH_BF2(norm_fwd_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), x, w, b, y, stats, T, D, eps);
   return TWIST_OK;
 }
@@ -478,7 +618,6 @@ size_t twist_colsum_partial_floats(int T, int n) { return (size_t)n_chunks(T) * 
 twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
                             int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D) {
   const int nc = n_chunks(T);
-  const auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   const int nv = D % 256 == 0 ? D / 256 : 0;
   const bool fused_ok = al16(dy) && al16(x) && al16(w) && al16(dx) && (!dxb || al16(dxb)) && (nv == 1 || nv == 2 || nv == 3 || nv == 4 || nv == 8 || (nv == 16 && rms && bf16));
   if (fused_ok) {
@@ -535,6 +674,12 @@ twist_status twist_rope_table(twist_ctx *ctx, float *tab, int N, int dh, float t
 }
 
 twist_status twist_rope_apply(twist_ctx *ctx, int bf16, void *qkv, const float *tab, int B, int N, int Hs, int dh, float sign) {
+  if (bf16 && dh % 16 == 0 && al16(qkv) && al16(tab)) {
+    const int64_t total8 = (int64_t)B * N * 2 * Hs * (dh / 16);
+    hipLaunchKernelGGL(rope_vec_kernel, grid1(total8), dim3(kT), 0, ctx->stream, static_cast<u32x4v *>(qkv), tab, N, Hs, dh, sign, total8);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   const int64_t total = (int64_t)B * N * 2 * Hs * (dh / 2);
   LAUNCH_BF(rope_kernel, bf16, grid1(total), dim3(kT), qkv, tab, N, Hs, dh, sign, total);
   return TWIST_OK;
@@ -542,12 +687,23 @@ twist_status twist_rope_apply(twist_ctx *ctx, int bf16, void *qkv, const float *
 
 twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F) {
   const int64_t total = (int64_t)T * F;
+  if (bf16 && act == TWIST_ACT_SWIGLU && F % 8 == 0 && al16(gu) && al16(a)) {
+    hipLaunchKernelGGL(swiglu_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), F / 8, total / 8);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   LAUNCH_BF(act_fwd_kernel, bf16, grid1(total), dim3(kT), act, gu, a, F, total);
   return TWIST_OK;
 }
 
 twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F) {
   const int64_t total = (int64_t)T * F;
+  if (bf16 && act == TWIST_ACT_SWIGLU && F % 8 == 0 && al16(gu) && al16(da) && al16(dgu)) {
+    hipLaunchKernelGGL(swiglu_bwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<const u32x4v *>(da),
+                       static_cast<u32x4v *>(dgu), F / 8, total / 8);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   LAUNCH_BF(act_bwd_kernel, bf16, grid1(total), dim3(kT), act, gu, da, dgu, F, total);
   return TWIST_OK;
 }
