@@ -65,6 +65,7 @@ def bench_train(args, tw, si, torch):
     layers, globs = device_weights(cfg, 0, si, torch)
     fw = tw.FullWeights(layers, globs)
     ctx = tw.Context(tw.desc_from_cfg(cfg))
+    ctx.twist_set_overlap(not args.no_overlap)
     plan0 = ctx.twist_sample(S, hs, fs, seed=0, rnd=0)
     nbytes = ctx.twist_subnet_bytes(plan0, tw.STORE_ADAMW)
     stor = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(S)]
@@ -134,7 +135,7 @@ def bench_train(args, tw, si, torch):
         ctx.twist_subnet_fwd_bwd(sub, xs[s * args.local_steps], ys[s * args.local_steps], ws, loss)
     n_gemm, gemm_ms, gemm_flops = ctx.twist_profile_gemm_read()
     ctx.twist_profile_gemm(False)
-    ctx.twist_set_overlap(True)
+    ctx.twist_set_overlap(not args.no_overlap)
     for sub in subs:
         sub.close()
     plan.close()
@@ -249,6 +250,7 @@ def main():
     ap.add_argument("--local-steps", type=int, default=10, help="AdamW steps per subnet per round")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-movers", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream also in the timed region (for per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the S subnets run back-to-back on it); use --gpus 1", file=sys.stderr)

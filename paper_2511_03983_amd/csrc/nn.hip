@@ -237,17 +237,23 @@ __global__ __launch_bounds__(kT) void norm_bwd_fused_kernel(const void *dy, cons
   }
 }
 
-// out[c] = alpha * sum_k partial[k*stride + c].  A workgroup owns 64 columns; its 256 threads are 4 chunk slices x
-// 64 columns, each summing every fourth chunk in ascending order, and the four slices are added in order at the end.
+// out[c] = alpha * sum_k partial[k*stride + c].  A workgroup owns 16 columns; its 256 threads are 16 chunk slices x
+// 16 columns, each summing every sixteenth chunk in ascending order; the slices are then added in order.
 __global__ __launch_bounds__(kT) void reduce_partial_kernel(const float *partial, int64_t stride, int n_chunks, float alpha, float *out, int n) {
-  __shared__ float sh[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63), slice = threadIdx.x >> 6;
+  __shared__ float sh[16][16];
+  const int col = threadIdx.x & 15, slice = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + col;
   float s = 0.f;
   if (c < n)
-    for (int k = slice; k < n_chunks; k += 4) s += partial[(int64_t)k * stride + c];
-  sh[slice][threadIdx.x & 63] = s;
+    for (int k = slice; k < n_chunks; k += 16) s += partial[(int64_t)k * stride + c];
+  sh[slice][col] = s;
   __syncthreads();
-  if (slice == 0 && c < n) out[c] = alpha * (sh[0][threadIdx.x] + sh[1][threadIdx.x] + sh[2][threadIdx.x] + sh[3][threadIdx.x]);
+  if (slice == 0 && c < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += sh[i][col];
+    out[c] = alpha * t;
+  }
 }
 
 template <int BF>
@@ -640,17 +646,17 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
     }
 #undef TW_NORM_FUSED
     TW_HIP(ctx, hipGetLastError());
-    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
-    if (db) hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
+    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+    if (db) hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
   // general shapes: parameter gradients first (they read dy and x, which the dx pass leaves untouched)
   LAUNCH_BF(norm_bwd_dw_kernel, bf16, dim3((D + 63) / 64, nc), dim3(64), dy, x, stats, partial, T, D);
-  hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+  hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
   TW_HIP(ctx, hipGetLastError());
   if (db) {
-    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 63) / 64), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
+    hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
     TW_HIP(ctx, hipGetLastError());
   }
   LAUNCH_BF2(norm_bwd_dx_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), dy, x, w, stats, dx, accumulate, dxb, T, D);
@@ -660,7 +666,7 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
 twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int n) {
   const int nc = n_chunks(T);
   LAUNCH_BF(colsum_kernel, bf16, dim3((n + 63) / 64, nc), dim3(64), src, ld, partial, T, n);
-  hipLaunchKernelGGL(reduce_partial_kernel, dim3((n + 63) / 64), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
+  hipLaunchKernelGGL(reduce_partial_kernel, dim3((n + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }
