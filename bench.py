@@ -58,6 +58,28 @@ def flops_fwd_bwd(cfg, hs, F, B, N):
     return 3 * (cfg.n_layers * per_layer + head)
 
 
+# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this benchmark's own command and
+# calibrated against streaming kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; the counter
+# sits behind the L2, so reads served by the Infinity Cache are included).  Source: profiles/bench_hbm_traffic_fetch_write.txt
+TRAFFIC_PROJECTION_LAUNCH = 289.6e6         # average over every projection launch of a forward+backward pass
+TRAFFIC_EXTRACT_LAYER_LAUNCH = 405.3e6      # one layer of one subnet at the 7B shape, unit-major layout
+TRAFFIC_AGGREGATE_LAYER_LAUNCH = 2029.7e6   # one layer, 8 subnets
+
+
+def bytes_fwd_bwd_projections(cfg, hs, F, B, N):
+    """Algorithmic bytes of the projection launches of one forward+backward: each operand read once, the output
+    written once (fp32 residual read and written where the epilogue adds it), and their number."""
+    T, d, hd, V = B * N, cfg.d_model, hs * cfg.d_head, cfg.vocab
+    nf = 2 if cfg.act == "swiglu" else 1
+    def g(m, n, k, out_b, resid=False):
+        return 2 * (m * k + k * n) + out_b * m * n + (4 * m * n if resid else 0)
+    per_layer = (g(T, 3 * hd, d, 2) + g(T, d, hd, 4, True) + g(T, nf * F, d, 2) + g(T, d, F, 4, True)        # forward
+                 + g(T, d, 3 * hd, 2) + g(T, hd, d, 2) + g(T, d, nf * F, 2) + g(T, F, d, 2)                    # input gradients
+                 + g(3 * hd, d, T, 4) + g(hd, d, T, 4) + g(nf * F, d, T, 4) + g(F, d, T, 4))                  # weight gradients
+    head = g(T, V, d, 2) + g(T, d, V, 2) + g(V, d, T, 4)
+    return cfg.n_layers * per_layer + head, cfg.n_layers * 12 + 3
+
+
 def bench_train(args, tw, si, torch):
     cfg = replace(si.CFG3, out_unit_major=True)      # output projections stored unit-major: every gather is a row gather
     S, hs, fs, B, N = 4, 8, 2816, 4, 2048
@@ -152,6 +174,8 @@ def bench_train(args, tw, si, torch):
                  "flops_per_launch": gemm_flops / max(n_gemm, 1)},
         "loss": loss.item(),
     }
+    pb, pn = bytes_fwd_bwd_projections(cfg, hs, fs, B, N)
+    res["gemm"]["algorithmic_bytes_per_launch"] = pb / pn
     del stor, ws, layers, globs, fw
     torch.cuda.empty_cache()
     return res
@@ -283,7 +307,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_pp_kernel / gemm_mfma_kernel: every projection launch of one forward+backward per subnet, "
                                                  "kernels serialised on one stream",
                      "achieved": g["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g["tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": None, "avg_launch_ms": g["avg_ms"], "launches": g["launches"], "flops_per_launch": g["flops_per_launch"]},
+                     "traffic": TRAFFIC_PROJECTION_LAUNCH, "traffic_unit": "bytes per launch behind the L2 (rocprofv3 FETCH_SIZE/WRITE_SIZE, calibrated)",
+                     "algorithmic_bytes_per_launch": g["algorithmic_bytes_per_launch"],
+                     "avg_launch_ms": g["avg_ms"], "launches": g["launches"], "flops_per_launch": g["flops_per_launch"]},
         "fwd_bwd": {"tokens_per_s": train["fwd_bwd_tokens_per_s"], "ms": train["fwd_bwd_ms"], "tflops": train["fwd_bwd_tflops"],
                     "frac_mfma_peak": train["fwd_bwd_frac_mfma_peak"]},
         "phase_ms_per_step": train["phase_ms_per_step"],
@@ -296,7 +322,9 @@ def main():
             "achieved": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) / ((movers["extract_ms"] + movers["aggregate_ms"]) * 1e-3),
             "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) / ((movers["extract_ms"] + movers["aggregate_ms"]) * 1e-3) / PEAK_HBM_GBS,
-            "traffic": None}
+            "traffic": 8 * TRAFFIC_EXTRACT_LAYER_LAUNCH + TRAFFIC_AGGREGATE_LAYER_LAUNCH,
+            "traffic_unit": "bytes per layer (8 extract launches + 1 aggregate launch) behind the L2",
+            "algorithmic_bytes_per_layer": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) * 1e9 / 32}
         out["movers_llama7b_stack_out_in_layout"] = movers_rm
     print(json.dumps(out), flush=True)
 
