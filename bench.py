@@ -236,6 +236,41 @@ def bench_movers(args, tw, si, torch, unit_major=True):
     return res
 
 
+def bench_golden_ticket(args, tw, si, torch):
+    """configs[4]: forward+backward of the Llama-7B-shaped stack pruned once to 16 of 32 heads and 5504 of 11008
+    neurons per layer (deployment extract, untimed), next to the unpruned stack at the same batch 2 x 4096."""
+    cfg = replace(si.CFG5, out_unit_major=True)
+    B, N = 2, 4096
+    layers, globs = device_weights(cfg, 2, si, torch)
+    fw = tw.FullWeights(layers, globs)
+    ctx = tw.Context(tw.desc_from_cfg(cfg))
+    tok = torch.randint(0, cfg.vocab, (B, N + 1), generator=torch.Generator(device="cuda").manual_seed(3), device="cuda", dtype=torch.int32)
+    x, y = tok[:, :-1].contiguous(), tok[:, 1:].contiguous()
+    loss = torch.zeros(1, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    res = {}
+    for tag, hs, fs in (("pruned", 16, 5504), ("unpruned", 32, 11008)):
+        plan = ctx.twist_sample(1, hs, fs, seed=5, require_coverage=False)
+        sub = ctx.twist_extract(plan, fw, 0, store=tw.STORE_GRADS)
+        ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        a = ev(); a.record()
+        reps = 3
+        for _ in range(reps):
+            ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        b = ev(); b.record(); torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        fl = flops_fwd_bwd(cfg, hs, fs, B, N)
+        res[tag] = {"fwd_bwd_ms": ms, "tokens_per_s": B * N / (ms * 1e-3), "tflops": fl / (ms * 1e-3) / 1e12,
+                    "frac_mfma_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "loss": loss.item()}
+        sub.close(); plan.close()
+        del ws, sub
+        torch.cuda.empty_cache()
+    res["speedup_pruned_over_unpruned"] = res["unpruned"]["fwd_bwd_ms"] / res["pruned"]["fwd_bwd_ms"]
+    res["ideal_flop_ratio"] = flops_fwd_bwd(cfg, 32, 11008, B, N) / flops_fwd_bwd(cfg, 16, 5504, B, N)
+    return res
+
+
 def cpu_baseline(si):
     """The CPU checker as it stands, timed on a bounded sample of the same workload: the Llama-1B-shaped
     half-width subnet at full widths and vocabulary with 1 and 2 layers on 2 x 1024 tokens; the per-layer
@@ -274,6 +309,7 @@ def main():
     ap.add_argument("--local-steps", type=int, default=10, help="AdamW steps per subnet per round")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-movers", action="store_true")
+    ap.add_argument("--skip-golden", action="store_true", help="skip the pruned-versus-unpruned 7B-shaped forward+backward leg")
     ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream also in the timed region (for per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -292,6 +328,8 @@ def main():
     log("[bench] movers (unit-major output projections):", json.dumps(movers))
     movers_rm = None if args.skip_movers else bench_movers(args, tw, si, torch, unit_major=False)
     log("[bench] movers ([out, in] output projections):", json.dumps(movers_rm))
+    golden = None if args.skip_golden else bench_golden_ticket(args, tw, si, torch)
+    log("[bench] golden ticket (7B shape, pruned vs unpruned):", json.dumps(golden))
     cpu = None if args.skip_cpu else cpu_baseline(si)
 
     g = train["gemm"]
@@ -326,6 +364,8 @@ def main():
             "traffic_unit": "bytes per layer (8 extract launches + 1 aggregate launch) behind the L2",
             "algorithmic_bytes_per_layer": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) * 1e9 / 32}
         out["movers_llama7b_stack_out_in_layout"] = movers_rm
+    if golden:
+        out["golden_ticket_llama7b_fwd_bwd"] = golden
     print(json.dumps(out), flush=True)
 
 
