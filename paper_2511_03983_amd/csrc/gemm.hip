@@ -527,7 +527,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
                         int64_t ldc, const GemmEpilogue &e, hipStream_t st) {
   if (M <= 0 || N <= 0 || K <= 0) return TWIST_OK;
-  const hipStream_t stream = st ? st : stream;
+  const hipStream_t stream = st ? st : ctx->stream;
   hipEvent_t ev_stop = nullptr;
   if (ctx->prof_gemm) {
     hipEvent_t ev_start;

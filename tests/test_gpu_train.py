@@ -209,3 +209,30 @@ def test_scale_mode_none_and_shape_errors(lib):
         ctx.twist_subnet_step(sub, lib.OPT_ADAMW)
     with pytest.raises(lib.TwistError):                      # sequence longer than max_seq
         ctx.twist_workspace_bytes(sub, 1, cfg.max_seq + 1)
+
+
+def test_work_is_enqueued_on_the_contexts_stream(lib):
+    """A context created on a non-default stream gives the same bits as one on the default stream (every kernel,
+    the second stream's included, is ordered on the stream the caller handed over)."""
+    cfg, S, hs, fs, B, N = CASES["llama_bf16"]
+    full_np = si.make_weights(cfg, 2, std=0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    x_np, y_np, x, y = _data(cfg, B, N, 5)
+    torch.cuda.synchronize()
+    results = []
+    for stream in (None, torch.cuda.Stream(), torch.cuda.Stream()):
+        ctx = lib.Context(lib.desc_from_cfg(cfg), stream=stream)
+        plan = ctx.twist_sample(S, hs, fs, seed=3)
+        fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+        sub = ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS)
+        ws = torch.zeros(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        loss = torch.zeros(1, device="cuda")
+        torch.cuda.synchronize()
+        for _ in range(2):
+            ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        torch.cuda.synchronize()
+        results.append((loss.item(), {k: sub.twist_subnet_view(1, k, GRAD).clone() for k in ("wq", "wo", "w_gate", "w_down", "norm1_w")}))
+    for other in results[1:]:
+        assert other[0] == results[0][0]
+        for k, g in results[0][1].items():
+            assert torch.equal(g, other[1][k]), k
