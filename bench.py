@@ -271,6 +271,44 @@ def bench_golden_ticket(args, tw, si, torch):
     return res
 
 
+def bench_latency_ablation(args, tw, si, torch):
+    """Latency study of Section 5 (Figure 4 / Table 2) on synthetic data: GPT-2-small shape, blocks = heads and
+    d_ff/12-neuron FFN blocks, first and last two layers shared, kept blocks kappa in {10, 8, 6, 4} of 12 for the
+    attention blocks, the FFN blocks, or both; milliseconds per batch of 2 x 1024 tokens for forward+backward+AdamW
+    on one subnet, next to the full-width model."""
+    cfg = replace(si.CFG2, ffn_granule=si.CFG2.d_ff // 12)
+    B, N = 2, 1024
+    layers, globs = device_weights(cfg, 4, si, torch)
+    fw = tw.FullWeights(layers, globs)
+    ctx = tw.Context(tw.desc_from_cfg(cfg))
+    shared = [1, 1] + [0] * (cfg.n_layers - 4) + [1, 1]
+    tok = torch.randint(0, cfg.vocab, (B, N + 1), generator=torch.Generator(device="cuda").manual_seed(6), device="cuda", dtype=torch.int32)
+    x, y = tok[:, :-1].contiguous(), tok[:, 1:].contiguous()
+    loss = torch.zeros(1, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def ms_per_batch(heads, ffn):
+        plan = ctx.twist_sample(3, heads, ffn, seed=1, layer_shared=shared, require_coverage=heads * 3 >= 12 and ffn * 3 >= 12)
+        sub = ctx.twist_extract(plan, fw, 0, store=tw.STORE_ADAMW)
+        ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+            ctx.twist_subnet_step(sub, tw.OPT_ADAMW, lr=1e-4)
+        a = ev(); a.record()
+        reps = 10
+        for _ in range(reps):
+            ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+            ctx.twist_subnet_step(sub, tw.OPT_ADAMW, lr=1e-4)
+        b = ev(); b.record(); torch.cuda.synchronize()
+        sub.close(); plan.close()
+        return a.elapsed_time(b) / reps
+
+    res = {"batch": [B, N], "full_width_ms": ms_per_batch(12, 12)}
+    for k in (10, 8, 6, 4):
+        res[f"kappa_{k}"] = {"attn_ms": ms_per_batch(k, 12), "ffn_ms": ms_per_batch(12, k), "both_ms": ms_per_batch(k, k)}
+    return res
+
+
 def cpu_baseline(si):
     """The CPU checker as it stands, timed on a bounded sample of the same workload: the Llama-1B-shaped
     half-width subnet at full widths and vocabulary with 1 and 2 layers on 2 x 1024 tokens; the per-layer
@@ -310,6 +348,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-movers", action="store_true")
     ap.add_argument("--skip-golden", action="store_true", help="skip the pruned-versus-unpruned 7B-shaped forward+backward leg")
+    ap.add_argument("--ablation", action="store_true", help="also run the GPT-2-small-shaped latency study (kept blocks 10/8/6/4 of 12)")
     ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream also in the timed region (for per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -330,6 +369,9 @@ def main():
     log("[bench] movers ([out, in] output projections):", json.dumps(movers_rm))
     golden = None if args.skip_golden else bench_golden_ticket(args, tw, si, torch)
     log("[bench] golden ticket (7B shape, pruned vs unpruned):", json.dumps(golden))
+    ablation = bench_latency_ablation(args, tw, si, torch) if args.ablation else None
+    if ablation:
+        log("[bench] latency ablation (GPT-2-small shape):", json.dumps(ablation))
     cpu = None if args.skip_cpu else cpu_baseline(si)
 
     g = train["gemm"]
@@ -366,6 +408,8 @@ def main():
         out["movers_llama7b_stack_out_in_layout"] = movers_rm
     if golden:
         out["golden_ticket_llama7b_fwd_bwd"] = golden
+    if ablation:
+        out["latency_ablation_gpt2_small"] = ablation
     print(json.dumps(out), flush=True)
 
 

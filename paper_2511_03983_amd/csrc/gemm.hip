@@ -1,7 +1,8 @@
 // Dense projections of the subnet: C = epilogue(op(A) op(B)) with fp32 accumulation.
-//  - bf16 operands: MFMA kernel (v_mfma_f32_32x32x16_bf16), 256x256x32 or 128x128x32 workgroup tiles,
-//    operands staged through LDS in their memory orientation; operands whose contraction index is the slow
-//    axis in memory are read back with the transposing LDS load.
+//  - bf16 operands: MFMA kernels (v_mfma_f32_32x32x16_bf16): a 256x256 ping-pong kernel fed by direct-to-LDS
+//    loads for all but the smallest products, and a 128x128 register-staged kernel; operands stay in LDS in their
+//    memory orientation, and those whose contraction index is the slow axis in memory are read back with the
+//    transposing LDS load.
 //  - anything else (fp32 models, unaligned shapes): a plain tiled FMA kernel with arbitrary strides.
 #include <algorithm>
 
@@ -502,18 +503,13 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
 
 template <int AKM, int BKM>
 void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
-  // 256x256 tiles (8 waves of 64x128) when they fill the chip, else 128x128 (4 waves of 64x64)
+  // the 256x256 ping-pong kernel (one persistent workgroup per CU) from 64 tiles up, else 128x128 tiles (4 waves of 64x64)
   const int big = ((M + 255) / 256) * ((N + 255) / 256);
   const char *force = getenv("TWIST_GEMM_TILE");  // test knob: "256" or "128" pins the tile size
   const bool use_big = force ? atoi(force) == 256 : big >= 64;
-  static const bool old_impl = getenv("TWIST_GEMM_OLD") != nullptr;  // test knob: the single-phase 256x256 kernel
-  if (use_big && !old_impl) {
+  if (use_big) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
-    static const int persist = getenv("TWIST_GEMM_PERSIST") ? atoi(getenv("TWIST_GEMM_PERSIST")) : 256;
-    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(std::min(tm * tn, persist)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
-  } else if (use_big) {
-    const int tm = (M + 255) / 256, tn = (N + 255) / 256;
-    hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 256, 256, 4, 2>), dim3(tm * tn), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(std::min(tm * tn, 256)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
   } else {
     const int tm = (M + 127) / 128, tn = (N + 127) / 128;
     hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 128, 128, 2, 2>), dim3(tm * tn), dim3(256), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);

@@ -236,3 +236,32 @@ def test_work_is_enqueued_on_the_contexts_stream(lib):
         assert other[0] == results[0][0]
         for k, g in results[0][1].items():
             assert torch.equal(g, other[1][k]), k
+
+
+def test_block_granular_subnet_with_shared_layers_matches_oracle(lib):
+    """The configuration of the paper's latency study (Section 5, "Setup"; Figure 4 / Table 2) at GPT-2-small width:
+    FFN blocks of d_ff/12 neurons, heads as blocks, first and last layer shared, 8 of 12 blocks kept, common blocks."""
+    cfg = replace(si.CFG2, n_layers=3, ffn_granule=256, max_seq=128)
+    S, hs, fs, B, N = 2, 8, 8, 1, 128
+    shared, ch, cf = [1, 0, 1], (0, 5), (3,)
+    full_np = si.make_weights(cfg, 7, std=0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=2, common_heads=ch, common_ffn=cf, layer_shared=shared)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 2, 0, ch, cf, shared)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    x_np, y_np, x, y = _data(cfg, B, N, 11)
+    loss = torch.zeros(1, device="cuda")
+    for s in range(S):
+        sub = ctx.twist_extract(plan, fw, s, store=lib.STORE_GRADS)
+        ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+        ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        torch.cuda.synchronize()
+        osub = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        assert osub["layers"][0]["w_up"].shape[0] == cfg.d_ff and osub["layers"][1]["w_up"].shape[0] == fs * cfg.ffn_granule
+        got = subnet_to_numpy(sub, cfg, GRAD)
+        oloss, ograds = omodel.forward_backward(cfg, osub, x_np, y_np)
+        rloss, rgrads = omodel.forward_backward(cfg, osub, x_np, y_np, q=_round_hook)
+        assert abs(loss.item() - oloss) <= 5e-3 * abs(oloss) and abs(loss.item() - rloss) <= 5e-3 * abs(rloss)
+        _compare_grads(cfg, got, ograds, 5e-3, "blocks/exact", fmt=(rgrads, ograds))
+        _compare_grads(cfg, got, rgrads, 5e-3, "blocks/rounded", fmt=(rgrads, ograds))
