@@ -32,6 +32,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
+// 2^x as the bare hardware instruction: results below the smallest normal number flush to zero, which is what a
+// probability that small is worth; the library routine's extra range handling costs five more instructions per value
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
-    const float alpha = exp2f(m - mn);
+    const float alpha = fast_exp2(m - mn);
     // probabilities, rounded to bf16 in pairs; the row sum is taken over the rounded values
     uint32_t pk[2][8];
     float sum = 0.f;
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const uint32_t u = pack2(exp2f(fmaf(s[mt][r], sc, -mn)), exp2f(fmaf(s[mt][r + 1], sc, -mn)));
+        const uint32_t u = pack2(fast_exp2(fmaf(s[mt][r], sc, -mn)), fast_exp2(fmaf(s[mt][r + 1], sc, -mn)));
         pk[mt][r >> 1] = u;
         sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
       }
@@ -256,7 +260,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float p = exp2f(fmaf(s[mt][r], sc, -L2));
+        float p = fast_exp2(fmaf(s[mt][r], sc, -L2));
         if (diag && kv > q) p = 0.f;
         s[mt][r] = p * (dp[mt][r] - dl) * scale;
       }
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int ql = mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);  // query row inside the tile
-        float p = exp2f(fmaf(s[mt][r], sc, -Ls[ql]));
+        float p = fast_exp2(fmaf(s[mt][r], sc, -Ls[ql]));
         if (diag && qt * 64 + ql < kv) p = 0.f;
         dp[mt][r] = p * (dp[mt][r] - Ds[ql]) * scale;  // dS
         s[mt][r] = p;
@@ -502,14 +506,14 @@ __global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, 
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
-    const float alpha = exp2f(m - mn);
+    const float alpha = fast_exp2(m - mn);
     uint32_t pk[2][8];
     float sum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const uint32_t u = pack2(exp2f(fmaf(s[mt][r], sc, -mn)), exp2f(fmaf(s[mt][r + 1], sc, -mn)));
+        const uint32_t u = pack2(fast_exp2(fmaf(s[mt][r], sc, -mn)), fast_exp2(fmaf(s[mt][r + 1], sc, -mn)));
         pk[mt][r >> 1] = u;
         sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
       }
@@ -618,7 +622,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_dl_kernel(const uint16_t *qk
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float p = exp2f(fmaf(s[r], sc, -L2));
+        float p = fast_exp2(fmaf(s[r], sc, -L2));
         if (diag && kv > q) p = 0.f;
         s[r] = p * (dp[r] - dl) * scale;
       }
@@ -715,7 +719,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * r4 + e;
-          float p = exp2f(fmaf(s[r], sc, -L4[e] * kLog2e));
+          float p = fast_exp2(fmaf(s[r], sc, -L4[e] * kLog2e));
           if (diag && qt * 64 + qrow + e < kv) p = 0.f;
           dp[r] = p * (dp[r] - D4[e]) * scale;  // dS
           s[r] = p;
