@@ -147,8 +147,12 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
-    const float alpha = fast_exp2(m - mn);
+    // The running maximum only has to keep 2^(s - m) in range, so it is raised (and the accumulators rescaled) only
+    // when some query of the wave would otherwise exceed 2^8; on most tiles nothing is rescaled.  The first tile
+    // always raises it: key 0 is visible to every query, so the new maximum is finite.
+    const float mcand = fmaxf(m, mx * sc);
+    const bool raise = __any(mcand > m + 8.f);
+    const float mn = raise ? mcand : m;
     // probabilities, rounded to bf16 in pairs; the row sum is taken over the rounded values
     uint32_t pk[2][8];
     float sum = 0.f;
@@ -158,14 +162,18 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
       for (int r = 0; r < 16; r += 2) {
         const uint32_t u = pack2(fast_exp2(fmaf(s[mt][r], sc, -mn)), fast_exp2(fmaf(s[mt][r + 1], sc, -mn)));
         pk[mt][r >> 1] = u;
-        sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
+        sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u), __builtin_bit_cast(bf16x2, 0x3f803f80u), sum, false);  // + both halves
       }
-    l = l * alpha + sum;
-    m = mn;
+    if (raise) {
+      const float alpha = fast_exp2(m - mn);
+      l *= alpha;
+      m = mn;
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    }
+    l += sum;
     // O^T[dh][q] += V^T[dh][kv] P^T[kv][q]
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -439,7 +447,8 @@ struct TileLoader {
 
 #define DL_WAIT_VM0 __builtin_amdgcn_s_waitcnt(0x0f70)
 
-__global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
+// two waves per SIMD (two workgroups per CU) is what lets one workgroup's softmax overlap the other's matrix work
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_fwd_dl_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
   const int nqb = N / 128, nbh = gridDim.x / nqb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -505,8 +514,12 @@ __global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mn = fmaxf(m, mx * sc);  // finite: key 0 is visible to every query and belongs to the first tile
-    const float alpha = fast_exp2(m - mn);
+    // The running maximum only has to keep 2^(s - m) in range, so it is raised (and the accumulators rescaled) only
+    // when some query of the wave would otherwise exceed 2^8; on most tiles nothing is rescaled.  The first tile
+    // always raises it: key 0 is visible to every query, so the new maximum is finite.
+    const float mcand = fmaxf(m, mx * sc);
+    const bool raise = __any(mcand > m + 8.f);
+    const float mn = raise ? mcand : m;
     uint32_t pk[2][8];
     float sum = 0.f;
 #pragma unroll
@@ -515,14 +528,18 @@ __global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, 
       for (int r = 0; r < 16; r += 2) {
         const uint32_t u = pack2(fast_exp2(fmaf(s[mt][r], sc, -mn)), fast_exp2(fmaf(s[mt][r + 1], sc, -mn)));
         pk[mt][r >> 1] = u;
-        sum += __uint_as_float(u << 16) + __uint_as_float(u & 0xffff0000u);
+        sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u), __builtin_bit_cast(bf16x2, 0x3f803f80u), sum, false);  // + both halves
       }
-    l = l * alpha + sum;
-    m = mn;
+    if (raise) {
+      const float alpha = fast_exp2(m - mn);
+      l *= alpha;
+      m = mn;
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    }
+    l += sum;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -554,7 +571,7 @@ __global__ __launch_bounds__(256) void flash_fwd_dl_kernel(const uint16_t *qkv, 
   if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
 }
 
-__global__ __launch_bounds__(256) void flash_bwd_dq_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_bwd_dq_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
                                                               uint16_t *dqkv, int N, int Hs, float scale) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
   const int nqb = N / 128, nbh = gridDim.x / nqb;
