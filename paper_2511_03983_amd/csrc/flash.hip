@@ -610,6 +610,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
   }
   dl += __shfl_xor(dl, 32, 64);
   if (g == 0) delta[((int64_t)b * Hs + h) * N + q] = dl;
+  const float dls = dl * scale;
   f32x16 acc[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -636,13 +637,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         s = MFMA(frag(Kt + mt * 8192, ro.fo[ks]), qf[ks], s);
         dp = MFMA(frag(Vt + mt * 8192, ro.fo[ks]), gf[ks], dp);
       }
+      if (diag) {  // tiles that straddle the diagonal: keys after the query get no weight
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float p = fast_exp2(fmaf(s[r], sc, -L2));
-        if (diag && kv > q) p = 0.f;
-        s[r] = p * (dp[r] - dl) * scale;
+        for (int r = 0; r < 16; ++r) {
+          const int kv = kt * 64 + mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (kv > q) s[r] = -INFINITY;
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], sc, -L2)) * fmaf(dp[r], scale, -dls);  // p (dp - delta) scale
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 df = pack8(s, 8 * t);
@@ -736,9 +739,10 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * r4 + e;
-          float p = fast_exp2(fmaf(s[r], sc, -L4[e] * kLog2e));
-          if (diag && qt * 64 + qrow + e < kv) p = 0.f;
-          dp[r] = p * (dp[r] - D4[e]) * scale;  // dS
+          float x = fmaf(s[r], sc, -L4[e] * kLog2e);
+          if (diag && qt * 64 + qrow + e < kv) x = -INFINITY;  // (the compiler keeps two copies of the loop body)
+          const float p = fast_exp2(x);
+          dp[r] = p * fmaf(dp[r], scale, -D4[e] * scale);  // dS
           s[r] = p;
         }
       }
