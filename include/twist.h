@@ -178,6 +178,12 @@ TWIST_API twist_status twist_workspace_bytes(twist_ctx *ctx, const twist_subnet 
 TWIST_API twist_status twist_subnet_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets,
                                   int32_t B, int32_t N, void *workspace, size_t workspace_bytes, float *loss_dev);
 
+/* Evaluation of an extracted subnet (Section 4.2, deployment: a pruned model is used as is): the forward half of
+ * twist_subnet_fwd_bwd only; *loss_dev receives the same loss.  Works on subnets extracted with any storage mode
+ * (no gradients are written); arguments, workspace and errors as for twist_subnet_fwd_bwd. */
+TWIST_API twist_status twist_subnet_forward(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets,
+                                            int32_t B, int32_t N, void *workspace, size_t workspace_bytes, float *loss_dev);
+
 /* Local optimizer step on every subnet parameter from the current gradients: SGD  w -= lr g,  or AdamW
  * (bias-corrected, decoupled decay on matrices only; needs TWIST_STORE_ADAMW).  bf16 models update fp32
  * master weights and re-round the bf16 copy. */

@@ -78,6 +78,7 @@ _SIGS = {
     "twist_subnet_destroy": ([_vp], None),
     "twist_workspace_bytes": ([_vp, _vp, _i32, _i32, C.POINTER(_sz)], _i32),
     "twist_subnet_fwd_bwd": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
+    "twist_subnet_forward": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
@@ -155,6 +156,12 @@ class Context:
                              loss: torch.Tensor) -> None:
         B, N = inputs.shape[0], inputs.shape[1]
         _check(lib.twist_subnet_fwd_bwd(self.h, sub.h, _vp(inputs.data_ptr()), _vp(targets.data_ptr()), B, N,
+                                        _vp(workspace.data_ptr()), workspace.numel(), _vp(loss.data_ptr())), self.h)
+
+    def twist_subnet_forward(self, sub: "Subnet", inputs: torch.Tensor, targets: torch.Tensor, workspace: torch.Tensor,
+                             loss: torch.Tensor) -> None:
+        B, N = inputs.shape[0], inputs.shape[1]
+        _check(lib.twist_subnet_forward(self.h, sub.h, _vp(inputs.data_ptr()), _vp(targets.data_ptr()), B, N,
                                         _vp(workspace.data_ptr()), workspace.numel(), _vp(loss.data_ptr())), self.h)
 
     def twist_subnet_step(self, sub: "Subnet", kind=OPT_SGD, lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0) -> None:

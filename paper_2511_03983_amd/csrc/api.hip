@@ -520,6 +520,13 @@ extern "C" twist_status twist_subnet_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, 
   return twist_train_fwd_bwd(ctx, sub, inputs, targets, B, N, workspace, workspace_bytes, loss_dev);
 }
 
+extern "C" twist_status twist_subnet_forward(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets, int32_t B, int32_t N,
+                                             void *workspace, size_t workspace_bytes, float *loss_dev) {
+  if (!ctx || !sub || !inputs || !targets || !workspace || !loss_dev) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_forward: null argument");
+  if (sub->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_forward: subnet belongs to another context");
+  return twist_train_fwd_bwd(ctx, sub, inputs, targets, B, N, workspace, workspace_bytes, loss_dev, true);
+}
+
 extern "C" twist_status twist_subnet_step(twist_ctx *ctx, twist_subnet *sub, const twist_opt_desc *opt) {
   if (!ctx || !sub || !opt) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_step: null argument");
   if (sub->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_step: subnet belongs to another context");

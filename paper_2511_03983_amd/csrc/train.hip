@@ -146,9 +146,9 @@ twist_status twist_train_workspace_bytes(twist_ctx *ctx, const twist_subnet *sub
 }
 
 twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets, int B, int N, void *ws,
-                                 size_t ws_bytes, float *loss_dev) {
+                                 size_t ws_bytes, float *loss_dev, bool forward_only) {
   TW_TRY(check_train_shape(ctx, sub, B, N));
-  if (!sub->grads) TW_FAIL(ctx, TWIST_ESHAPE, "fwd_bwd: subnet was extracted without gradient storage");
+  if (!forward_only && !sub->grads) TW_FAIL(ctx, TWIST_ESHAPE, "fwd_bwd: subnet was extracted without gradient storage");
   if (reinterpret_cast<uintptr_t>(ws) % 256) TW_FAIL(ctx, TWIST_ESHAPE, "fwd_bwd: workspace must be 256-byte aligned");
   Workspace w;
   carve(ctx, sub, B, N, ws, w);
@@ -208,6 +208,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
                           d.norm_eps));
     TW_TRY(gemm(GEMM_NT, T, V, D, w.hf, D, P(wout), D, w.logits, w.ld_logits, 0));
     TW_TRY(twist_ce_fwd_bwd(ctx, bf, w.logits, w.ld_logits, static_cast<const int32_t *>(targets), w.rowloss, loss_dev, T, V));
+    if (forward_only) return TWIST_OK;
     // projection weight gradient, then the gradient flowing back into the final norm
     TW_TRY(gemm(GEMM_TN, V, D, T, w.logits, w.ld_logits, w.hf, D, G(wout), D, 1));
     TW_TRY(gemm(GEMM_NN, T, D, V, w.logits, w.ld_logits, P(wout), D, w.dh, D, 0));
@@ -215,6 +216,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
                           G(L.global[TWIST_FINAL_NORM_W]), G(L.global[TWIST_FINAL_NORM_B]), w.partial, T, D));
   } else {
     TW_TRY(twist_mse_fwd_bwd(ctx, bf, x_last, targets, w.dx, w.dxb, w.rowloss, loss_dev, (int64_t)T * D));
+    if (forward_only) return TWIST_OK;
   }
 
   // ------------------------------------------------------------------------------------ backward through the layers

@@ -265,3 +265,28 @@ def test_block_granular_subnet_with_shared_layers_matches_oracle(lib):
         assert abs(loss.item() - oloss) <= 5e-3 * abs(oloss) and abs(loss.item() - rloss) <= 5e-3 * abs(rloss)
         _compare_grads(cfg, got, ograds, 5e-3, "blocks/exact", fmt=(rgrads, ograds))
         _compare_grads(cfg, got, rgrads, 5e-3, "blocks/rounded", fmt=(rgrads, ograds))
+
+
+@pytest.mark.parametrize("name", ["gpt_f32", "llama_bf16_um"])
+def test_forward_only_evaluation_of_a_deployed_subnet(lib, name):
+    """twist_subnet_forward on a deployment-mode extract (weights only, no coverage requirement) gives the checker's
+    loss, and the same loss as the training entry point."""
+    cfg, S, hs, fs, B, N = CASES[name]
+    full_np = si.make_weights(cfg, 3, std=0.05 if cfg.dtype == "f32" else 0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(1, hs, fs, seed=9, require_coverage=False)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, 1, hs, fs, 9, require_coverage=False)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    x_np, y_np, x, y = _data(cfg, B, N, 4)
+    sub = ctx.twist_extract(plan, fw, 0)                      # weights only
+    ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    ctx.twist_subnet_forward(sub, x, y, ws, loss)
+    want = omodel.forward_loss(cfg, omove.extract(full_np, oplan, 0, cfg.d_head, cfg.ffn_granule), x_np, y_np)
+    tol = 5e-3 if cfg.dtype == "bf16" else 1e-4
+    assert abs(loss.item() - want) <= tol * abs(want), (loss.item(), want)
+    sub2 = ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS)
+    loss2 = torch.zeros(1, device="cuda")
+    ctx.twist_subnet_fwd_bwd(sub2, x, y, ws, loss2)
+    assert loss2.item() == loss.item()
