@@ -178,6 +178,15 @@ TWIST_API twist_status twist_workspace_bytes(twist_ctx *ctx, const twist_subnet 
 TWIST_API twist_status twist_subnet_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets,
                                   int32_t B, int32_t N, void *workspace, size_t workspace_bytes, float *loss_dev);
 
+/* Masked TwIST (Section 4.1): forward+backward of the FULL-width model `full_sub` (a subnet extracted from a plan
+ * that keeps every block) with the blocks that row s of `plan` does not name masked out, and the module scales of
+ * row s's widths.  Loss and the gradients of the kept blocks equal those of the subnet twist_extract(plan, s)
+ * would give; gradients of masked blocks are zero; shared tensors get their usual gradients.  Other arguments as
+ * for twist_subnet_fwd_bwd.  TWIST_ESHAPE if full_sub does not hold every block. */
+TWIST_API twist_status twist_subnet_fwd_bwd_masked(twist_ctx *ctx, twist_subnet *full_sub, const twist_plan *plan, int32_t s,
+                                                   const void *inputs, const void *targets, int32_t B, int32_t N, void *workspace,
+                                                   size_t workspace_bytes, float *loss_dev);
+
 /* Evaluation of an extracted subnet (Section 4.2, deployment: a pruned model is used as is): the forward half of
  * twist_subnet_fwd_bwd only; *loss_dev receives the same loss.  Works on subnets extracted with any storage mode
  * (no gradients are written); arguments, workspace and errors as for twist_subnet_fwd_bwd. */

@@ -79,6 +79,7 @@ _SIGS = {
     "twist_workspace_bytes": ([_vp, _vp, _i32, _i32, C.POINTER(_sz)], _i32),
     "twist_subnet_fwd_bwd": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_forward": ([_vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
+    "twist_subnet_fwd_bwd_masked": ([_vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
@@ -157,6 +158,12 @@ class Context:
         B, N = inputs.shape[0], inputs.shape[1]
         _check(lib.twist_subnet_fwd_bwd(self.h, sub.h, _vp(inputs.data_ptr()), _vp(targets.data_ptr()), B, N,
                                         _vp(workspace.data_ptr()), workspace.numel(), _vp(loss.data_ptr())), self.h)
+
+    def twist_subnet_fwd_bwd_masked(self, full_sub: "Subnet", plan: "Plan", s: int, inputs: torch.Tensor, targets: torch.Tensor,
+                                    workspace: torch.Tensor, loss: torch.Tensor) -> None:
+        B, N = inputs.shape[0], inputs.shape[1]
+        _check(lib.twist_subnet_fwd_bwd_masked(self.h, full_sub.h, plan.h, s, _vp(inputs.data_ptr()), _vp(targets.data_ptr()), B, N,
+                                               _vp(workspace.data_ptr()), workspace.numel(), _vp(loss.data_ptr())), self.h)
 
     def twist_subnet_forward(self, sub: "Subnet", inputs: torch.Tensor, targets: torch.Tensor, workspace: torch.Tensor,
                              loss: torch.Tensor) -> None:

@@ -520,6 +520,14 @@ extern "C" twist_status twist_subnet_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, 
   return twist_train_fwd_bwd(ctx, sub, inputs, targets, B, N, workspace, workspace_bytes, loss_dev);
 }
 
+extern "C" twist_status twist_subnet_fwd_bwd_masked(twist_ctx *ctx, twist_subnet *full_sub, const twist_plan *plan, int32_t s, const void *inputs,
+                                                    const void *targets, int32_t B, int32_t N, void *workspace, size_t workspace_bytes, float *loss_dev) {
+  if (!ctx || !full_sub || !plan || !inputs || !targets || !workspace || !loss_dev) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_fwd_bwd_masked: null argument");
+  if (full_sub->ctx != ctx || plan->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_fwd_bwd_masked: subnet or plan belongs to another context");
+  if (s < 0 || s >= plan->S) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_fwd_bwd_masked: blueprint row %d outside [0, %d)", s, plan->S);
+  return twist_train_fwd_bwd(ctx, full_sub, inputs, targets, B, N, workspace, workspace_bytes, loss_dev, false, plan, s);
+}
+
 extern "C" twist_status twist_subnet_forward(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets, int32_t B, int32_t N,
                                              void *workspace, size_t workspace_bytes, float *loss_dev) {
   if (!ctx || !sub || !inputs || !targets || !workspace || !loss_dev) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_forward: null argument");

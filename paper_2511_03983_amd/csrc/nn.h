@@ -60,6 +60,9 @@ twist_status twist_ce_fwd_bwd(twist_ctx *ctx, int bf16, void *logits, int64_t ld
 // dx = 2 (x - y)/n ; dxb = activation-type copy; loss = mean squared error
 twist_status twist_mse_fwd_bwd(twist_ctx *ctx, int bf16, const float *x, const void *y, float *dx, void *dxb, float *partial, float *loss, int64_t n);
 
+// x [T, n_units*unit] (activation type): columns of the units u with keep[u] < 0 are set to zero
+twist_status twist_mask_cols(twist_ctx *ctx, int bf16, void *x, const int32_t *keep, int T, int n_units, int unit);
+
 twist_status twist_sgd(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, int64_t n, float lr);
 twist_status twist_adamw(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,
                          float lr, float b1, float b2, float eps, float wd, int64_t step);

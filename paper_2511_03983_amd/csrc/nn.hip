@@ -542,6 +542,14 @@ __global__ __launch_bounds__(kT) void norm_fwd_vec_kernel(const float *x, const 
   if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
 }
 
+template <int BF>
+__global__ __launch_bounds__(kT) void mask_cols_kernel(void *x, const int32_t *keep, int ncols, int unit, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % ncols);
+  if (keep[c / unit] < 0) El<BF>::st(x, i, 0.f);
+}
+
 inline dim3 grid1(int64_t n) { return dim3((unsigned)((n + kT - 1) / kT)); }
 
 }  // namespace
@@ -738,5 +746,11 @@ twist_status twist_adamw(twist_ctx *ctx, int bf16, void *params, float *master, 
                          float lr, float b1, float b2, float eps, float wd, int64_t step) {
   const double bc1 = 1.0 - pow((double)b1, (double)step), bc2 = 1.0 - pow((double)b2, (double)step);
   LAUNCH_BF(adamw_kernel, bf16, grid1(n), dim3(kT), params, master, grads, m, v, n, n_decay, lr, b1, b2, eps, wd, (float)(1.0 / bc1), (float)(1.0 / bc2));
+  return TWIST_OK;
+}
+
+twist_status twist_mask_cols(twist_ctx *ctx, int bf16, void *x, const int32_t *keep, int T, int n_units, int unit) {
+  const int64_t total = (int64_t)T * n_units * unit;
+  LAUNCH_BF(mask_cols_kernel, bf16, grid1(total), dim3(kT), x, keep, n_units * unit, unit, total);
   return TWIST_OK;
 }

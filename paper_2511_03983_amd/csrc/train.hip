@@ -146,7 +146,7 @@ twist_status twist_train_workspace_bytes(twist_ctx *ctx, const twist_subnet *sub
 }
 
 twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets, int B, int N, void *ws,
-                                 size_t ws_bytes, float *loss_dev, bool forward_only) {
+                                 size_t ws_bytes, float *loss_dev, bool forward_only, const twist_plan *mask_plan, int mask_row) {
   TW_TRY(check_train_shape(ctx, sub, B, N));
   if (!forward_only && !sub->grads) TW_FAIL(ctx, TWIST_ESHAPE, "fwd_bwd: subnet was extracted without gradient storage");
   if (reinterpret_cast<uintptr_t>(ws) % 256) TW_FAIL(ctx, TWIST_ESHAPE, "fwd_bwd: workspace must be 256-byte aligned");
@@ -162,6 +162,22 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   const int nf = d.act == TWIST_ACT_SWIGLU ? 2 : 1;
   const bool lm = d.vocab > 0;
   const bool um = d.out_unit_major != 0;  // output projections stored [in, out]: the three GEMM forms rotate
+  // Masked variant (Section 4.1, "Masked TwIST"): `sub` is a full-width subnet and the blocks that row `mask_row` of
+  // `mask_plan` does not name are zeroed where they enter the output projections (attention output columns,
+  // FFN activations) and where the gradient comes back through the same places; the module scales are those of
+  // the masked widths.  Everything else is the ordinary pass.
+  if (mask_plan) {
+    for (int l = 0; l < d.n_layers; ++l)
+      if (L.heads_sub[l] != d.n_heads || L.ffn_sub[l] != ctx->n_ffn_units())
+        TW_FAIL(ctx, TWIST_ESHAPE, "masked pass: the subnet must hold every block of layer %d", l);
+  }
+  auto mask = [&](void *x, int l, int kind, int unit) -> twist_status {  // zero the columns of x [T, n_full*unit] of blocks not kept
+    if (!mask_plan) return TWIST_OK;
+    const PlanEntry &pe = mask_plan->at(l, kind);
+    return twist_mask_cols(ctx, bf, x, pe.d_inv + (size_t)mask_row * pe.n_full, T, pe.n_full, unit);
+  };
+  auto kept = [&](int l, int kind, int full) { return mask_plan ? mask_plan->at(l, kind).n_sub : full; };
+  const int scale_mode = mask_plan ? mask_plan->scale_mode : sub->plan->scale_mode;
   auto P = [&](const Slot &s) -> void * { return s.off < 0 ? nullptr : sub->params + s.off * es; };
   auto G = [&](const Slot &s) -> float * { return s.off < 0 ? nullptr : sub->grads + s.off; };
   auto gemm = [&](GemmLayout lay, int M, int Nn, int K, const void *A, int64_t lda, const void *Bm, int64_t ldb, void *out, int64_t ldc, int out_f32,
@@ -182,19 +198,21 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
 
   for (int l = 0; l < d.n_layers; ++l) {
     const int Hs = L.heads_sub[l], HD = Hs * dh, F = L.ffn_sub[l] * d.ffn_granule;
-    const float c_a = sub->plan->scale_mode ? sqrtf((float)d.n_heads / (float)Hs) : 1.f;
-    const float c_f = sub->plan->scale_mode ? sqrtf((float)ctx->n_ffn_units() / (float)L.ffn_sub[l]) : 1.f;
+    const float c_a = scale_mode ? sqrtf((float)d.n_heads / (float)kept(l, TWIST_KIND_HEAD, Hs)) : 1.f;
+    const float c_f = scale_mode ? sqrtf((float)ctx->n_ffn_units() / (float)kept(l, TWIST_KIND_FFN, L.ffn_sub[l])) : 1.f;
     const LayerBufs &b = w.layer[l];
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), P(L.at(l, TWIST_NORM1_B)), b.h1, w.stats[2 * l], T, D, d.norm_eps));
     TW_TRY(gemm(GEMM_NT, T, 3 * HD, D, b.h1, D, P(L.at(l, TWIST_WQ)), D, b.qkv, 3 * HD, 0, 1.f, P(L.at(l, TWIST_BQ))));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, b.qkv, w.rope_tab, B, N, Hs, dh, 1.f));
     TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.o32, b.lse, B, N, Hs, dh));
+    TW_TRY(mask(b.o, l, TWIST_KIND_HEAD, dh));
     if (um) TW_TRY(gemm(GEMM_NN, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), D, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     else TW_TRY(gemm(GEMM_NT, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), HD, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), P(L.at(l, TWIST_NORM2_B)), b.h2, w.stats[2 * l + 1], T, D, d.norm_eps));
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     TW_TRY(gemm(GEMM_NT, T, nf * F, D, b.h2, D, P(w1), D, b.gu, nf * F, 0, 1.f, P(L.at(l, TWIST_B_UP))));
     TW_TRY(twist_act_fwd(ctx, bf, d.act, b.gu, b.a, T, F));
+    TW_TRY(mask(b.a, l, TWIST_KIND_FFN, d.ffn_granule));
     if (um) TW_TRY(gemm(GEMM_NN, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), D, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
     else TW_TRY(gemm(GEMM_NT, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), F, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
   }
@@ -230,8 +248,8 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   void *gx = w.dxb, *gx_other = w.dxb2;  // gradient of the residual stream in activation type: current, spare
   for (int l = d.n_layers - 1; l >= 0; --l) {
     const int Hs = L.heads_sub[l], HD = Hs * dh, F = L.ffn_sub[l] * d.ffn_granule;
-    const float c_a = sub->plan->scale_mode ? sqrtf((float)d.n_heads / (float)Hs) : 1.f;
-    const float c_f = sub->plan->scale_mode ? sqrtf((float)ctx->n_ffn_units() / (float)L.ffn_sub[l]) : 1.f;
+    const float c_a = scale_mode ? sqrtf((float)d.n_heads / (float)kept(l, TWIST_KIND_HEAD, Hs)) : 1.f;
+    const float c_f = scale_mode ? sqrtf((float)ctx->n_ffn_units() / (float)kept(l, TWIST_KIND_FFN, L.ffn_sub[l])) : 1.f;
     const LayerBufs &b = w.layer[l];
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     // FFN branch: y = c_f (a W_down^T + b_down)
@@ -242,6 +260,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.done(0));
     if (um) TW_TRY(gemm(GEMM_NT, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), D, w.da, F, 0, c_f));
     else TW_TRY(gemm(GEMM_NN, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
+    TW_TRY(mask(w.da, l, TWIST_KIND_FFN, d.ffn_granule));
     TW_TRY(side.wait_done(1));
     TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F));
     if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), w.partial, T, nf * F));
@@ -260,6 +279,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.done(2));
     if (um) TW_TRY(gemm(GEMM_NT, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), D, w.dout, HD, 0, c_a));
     else TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
+    TW_TRY(mask(w.dout, l, TWIST_KIND_HEAD, dh));
     TW_TRY(side.wait_done(3));
     TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, w.dqkv, w.rope_tab, B, N, Hs, dh, -1.f));

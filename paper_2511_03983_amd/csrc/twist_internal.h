@@ -132,5 +132,6 @@ twist_status twist_launch_zero(twist_ctx *ctx, void *dst, size_t bytes);
 // ---------------------------------------------------------------------------------------------- training
 twist_status twist_train_workspace_bytes(twist_ctx *ctx, const twist_subnet *sub, int B, int N, size_t *bytes);
 twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *inputs, const void *targets, int B,
-                                 int N, void *ws, size_t ws_bytes, float *loss_dev, bool forward_only = false);
+                                 int N, void *ws, size_t ws_bytes, float *loss_dev, bool forward_only = false,
+                                 const twist_plan *mask_plan = nullptr, int mask_row = 0);
 twist_status twist_train_step(twist_ctx *ctx, twist_subnet *sub, const twist_opt_desc *opt);

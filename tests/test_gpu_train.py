@@ -290,3 +290,53 @@ def test_forward_only_evaluation_of_a_deployed_subnet(lib, name):
     loss2 = torch.zeros(1, device="cuda")
     ctx.twist_subnet_fwd_bwd(sub2, x, y, ws, loss2)
     assert loss2.item() == loss.item()
+
+
+@pytest.mark.parametrize("name", ["gpt_f32", "llama_f32_um", "llama_bf16", "gpt_bf16_um"])
+def test_masked_full_model_equals_the_extracted_subnet(lib, name):
+    """Masked TwIST (Section 4.1): the full-width model with the unsampled blocks masked gives the loss of the
+    extracted subnet, the same gradients for the kept blocks and the shared tensors, and zero for the masked blocks."""
+    cfg, S, hs, fs, B, N = CASES[name]
+    bf = cfg.dtype == "bf16"
+    tol = 5e-3 if bf else 1e-4
+    full_np = si.make_weights(cfg, 5, std=0.05 if not bf else 0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=4)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 4)
+    whole = ctx.twist_sample(1, cfg.n_heads, cfg.n_ffn_units, seed=0, require_coverage=False)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    full_sub = ctx.twist_extract(whole, fw, 0, store=lib.STORE_GRADS)
+    x_np, y_np, x, y = _data(cfg, B, N, 6)
+    ws = torch.empty(ctx.twist_workspace_bytes(full_sub, B, N), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    for s in range(S):
+        ctx.twist_subnet_fwd_bwd_masked(full_sub, plan, s, x, y, ws, loss)
+        torch.cuda.synchronize()
+        got = subnet_to_numpy(full_sub, cfg, GRAD)
+        osub = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+        oloss, ograds = omodel.forward_backward(cfg, osub, x_np, y_np)
+        fmt = None
+        if bf:
+            _, rgrads = omodel.forward_backward(cfg, osub, x_np, y_np, q=_round_hook)
+            fmt = (rgrads, ograds)
+        assert abs(loss.item() - oloss) <= tol * abs(oloss)
+        # cut the full-shape gradients down to the subnet's blocks, check the rest is exactly zero
+        cut = {"layers": [], "globals": got["globals"]}
+        for l in range(cfg.n_layers):
+            lw = {}
+            for k, g in got["layers"][l].items():
+                ka = omove.PARTITIONED.get(k)
+                if ka is None:
+                    lw[k] = g
+                    continue
+                kind, axis = ka
+                q = cfg.d_head if kind == 0 else cfg.ffn_granule
+                e = omove.element_index(oplan[l][kind]["idx"][s], q)
+                rest = np.setdiff1d(np.arange(g.shape[axis]), e)
+                lw[k] = np.take(g, e, axis=axis)
+                assert not np.take(g, rest, axis=axis).any(), (l, k)
+            cut["layers"].append(lw)
+        _compare_grads(cfg, cut, ograds, tol, name + "/masked", fmt=fmt)
+    with pytest.raises(lib.TwistError):      # a partial subnet cannot stand in for the full model
+        ctx.twist_subnet_fwd_bwd_masked(ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS), plan, 0, x, y, ws, loss)
