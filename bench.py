@@ -198,7 +198,10 @@ def bench_movers(args, tw, si, torch, unit_major=True):
     ag_bytes = 2 * (S * (kept + shared) + part + shared)   # read every subnet element + write every central element
     gen = torch.Generator(device="cuda").manual_seed(7)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    ex_ms, ag_ms = [], []
+    ex_ms, ag_ms, rs_ms = [], [], []
+    image = torch.empty(ctx.twist_aggregate_image_bytes(), dtype=torch.uint8, device="cuda")
+    # running-sum form: per added element read 2 B + write 4 B (+ read 4 B unless first owner); finish reads 4 B, writes 2 B
+    rs_bytes = (2 + 4) * S * (kept + shared) + 4 * (S * (kept + shared) - (part + shared)) + (4 + 2) * (part + shared)
     reps = max(3, args.steps)
     for it in range(2 + reps):
         a = ev(); a.record()
@@ -213,13 +216,20 @@ def bench_movers(args, tw, si, torch, unit_major=True):
         c0 = ev(); c0.record()
         ctx.twist_aggregate(plan, subs, fw)
         d = ev(); d.record()
+        acc = ctx.twist_aggregate_begin(plan, image)      # the same aggregation, one subnet at a time
+        for sub in subs:
+            acc.twist_aggregate_add(sub)
+        acc.twist_aggregate_finish(fw)
+        e = ev(); e.record()
         torch.cuda.synchronize()
+        acc.close()
         if it >= 2:
-            ex_ms.append(a.elapsed_time(b)); ag_ms.append(c0.elapsed_time(d))
+            ex_ms.append(a.elapsed_time(b)); ag_ms.append(c0.elapsed_time(d)); rs_ms.append(d.elapsed_time(e))
     n_launch_ex = S * (cfg.n_layers + 0)
     med = lambda v: sorted(v)[len(v) // 2]
     res = {"extract_ms": med(ex_ms), "aggregate_ms": med(ag_ms), "extract_GBps": ex_bytes / med(ex_ms) / 1e6, "aggregate_GBps": ag_bytes / med(ag_ms) / 1e6,
            "extract_alg_GB": ex_bytes / 1e9, "aggregate_alg_GB": ag_bytes / 1e9,
+           "running_sum_aggregate_ms": med(rs_ms), "running_sum_aggregate_GBps": rs_bytes / med(rs_ms) / 1e6, "running_sum_alg_GB": rs_bytes / 1e9,
            "extract_launches": n_launch_ex, "aggregate_launches": cfg.n_layers,
            "extract_frac_hbm_peak": ex_bytes / med(ex_ms) / 1e6 / PEAK_HBM_GBS, "aggregate_frac_hbm_peak": ag_bytes / med(ag_ms) / 1e6 / PEAK_HBM_GBS}
     # plain device copy of known size, the practical ceiling the fractions should be read against
@@ -231,7 +241,7 @@ def bench_movers(args, tw, si, torch, unit_major=True):
         y.copy_(x)
     b = ev(); b.record(); torch.cuda.synchronize()
     res["copy_ceiling_GBps"] = 2 * x.numel() * 5 / a.elapsed_time(b) / 1e6
-    del x, y, stor, layers, fw
+    del x, y, stor, layers, fw, image
     torch.cuda.empty_cache()
     return res
 

@@ -120,6 +120,15 @@ typedef struct {
 typedef struct twist_ctx twist_ctx;
 typedef struct twist_plan twist_plan;
 typedef struct twist_subnet twist_subnet;
+typedef struct twist_accum twist_accum;
+
+/* One TwIST round (Section 3: sample, dispatch, local training for the repartition interval, aggregate). */
+typedef struct {
+  twist_sample_desc sample; /* blueprint of this round; advance sample.round from one round to the next  */
+  twist_opt_desc opt;       /* local optimizer; AdamW moments start at zero in every round                */
+  int32_t local_steps;      /* batches each subnet trains on before aggregation (repartition interval)  */
+  int32_t B, N;             /* batch shape of every local step                                          */
+} twist_round_desc;
 
 /* Create a context for one model shape.  hip_stream is a hipStream_t (NULL = the default stream).
  * TWIST_ESHAPE if a dimension is not positive, d_ff is not a multiple of ffn_granule, or d_head is odd
@@ -205,6 +214,33 @@ TWIST_API twist_status twist_subnet_step(twist_ctx *ctx, twist_subnet *sub, cons
  * once to desc.dtype; a parameter with a single owner is copied bit-exactly.  Updates `inout` in place. */
 TWIST_API twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, twist_subnet *const *subs, int32_t n_subs,
                              const twist_full_weights *inout);
+
+/* The same aggregation (Section 3.3) one subnet at a time, so that only one subnet needs to be resident: an fp32
+ * image of the central model accumulates p_i for every subnet added; finish divides by the number of added
+ * owners, rounds once to desc.dtype and writes the central tensors (a parameter none of the added subnets holds
+ * keeps its value), then forgets the added rows so the object can serve the next round of the same plan.
+ * Additions happen in the order of the add calls, hence the result is bit-identical to twist_aggregate over
+ * the same subnets in the same order.  `image` (dev, 256-byte aligned, >= twist_aggregate_image_bytes, caller-owned,
+ * need not be cleared) must stay valid until finish; a subnet's storage may be reused as soon as its add call has
+ * returned (stream order).  TWIST_EINVAL if a blueprint row is added twice or the subnet is from another plan. */
+TWIST_API twist_status twist_aggregate_image_bytes(twist_ctx *ctx, size_t *bytes);
+TWIST_API twist_status twist_aggregate_begin(twist_ctx *ctx, const twist_plan *plan, void *image, size_t image_bytes, twist_accum **out);
+TWIST_API twist_status twist_aggregate_add(twist_accum *acc, const twist_subnet *sub);
+TWIST_API twist_status twist_aggregate_finish(twist_accum *acc, const twist_full_weights *inout);
+TWIST_API void twist_aggregate_destroy(twist_accum *acc);
+
+/* One whole round on the persistent central model `inout` (Section 3; Section 5 resamples every few batches):
+ * sample the round's blueprint, then for s = 0..S-1: extract subnet s, run local_steps x {fwd_bwd, step} on its own
+ * batches, add it to the running aggregate; finally write the averaged parameters back.  One subnet is resident at
+ * a time, in `subnet_storage`.  inputs/targets (dev) hold S * local_steps batches back to back, subnet-major
+ * ([S][local_steps][B][N] token ids, or [..][B][N][d_model] activations when vocab = 0); loss_dev (dev) receives
+ * the S * local_steps losses in the same order.  Buffer sizes from twist_round_bytes; all buffers caller-owned.
+ * Synchronises the context's stream before returning (the round's index tables are released). */
+TWIST_API twist_status twist_round_bytes(twist_ctx *ctx, const twist_round_desc *rd, size_t *subnet_bytes, size_t *workspace_bytes,
+                                         size_t *image_bytes);
+TWIST_API twist_status twist_round(twist_ctx *ctx, const twist_round_desc *rd, const twist_full_weights *inout, const void *inputs,
+                                   const void *targets, void *subnet_storage, size_t subnet_bytes, void *workspace,
+                                   size_t workspace_bytes, void *image, size_t image_bytes, float *loss_dev);
 
 /* Kernel-level entry point for tests and benchmarks: one projection of the subnet forward/backward pass in
  * isolation, C = alpha * op(A) op(B), fp32 accumulation, on the ctx's stream (Appendix A.1: Q_h = X W^Q_h etc.;

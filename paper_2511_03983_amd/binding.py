@@ -63,6 +63,10 @@ class OptDesc(C.Structure):
                 ("weight_decay", C.c_float)]
 
 
+class RoundDesc(C.Structure):
+    _fields_ = [("sample", SampleDesc), ("opt", OptDesc), ("local_steps", C.c_int32), ("B", C.c_int32), ("N", C.c_int32)]
+
+
 _vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
 _PI32 = C.POINTER(C.c_int32)
 _SIGS = {
@@ -82,6 +86,13 @@ _SIGS = {
     "twist_subnet_fwd_bwd_masked": ([_vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _sz, _vp], _i32),
     "twist_subnet_step": ([_vp, _vp, C.POINTER(OptDesc)], _i32),
     "twist_aggregate": ([_vp, _vp, C.POINTER(_vp), _i32, C.POINTER(FullWeightsC)], _i32),
+    "twist_aggregate_image_bytes": ([_vp, C.POINTER(_sz)], _i32),
+    "twist_aggregate_begin": ([_vp, _vp, _vp, _sz, C.POINTER(_vp)], _i32),
+    "twist_aggregate_add": ([_vp, _vp], _i32),
+    "twist_aggregate_finish": ([_vp, C.POINTER(FullWeightsC)], _i32),
+    "twist_aggregate_destroy": ([_vp], None),
+    "twist_round_bytes": ([_vp, C.POINTER(RoundDesc), C.POINTER(_sz), C.POINTER(_sz), C.POINTER(_sz)], _i32),
+    "twist_round": ([_vp, C.POINTER(RoundDesc), C.POINTER(FullWeightsC), _vp, _vp, _vp, _sz, _vp, _sz, _vp, _sz, _vp], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
     "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
@@ -179,6 +190,46 @@ class Context:
         arr = (_vp * len(subs))(*[s.h for s in subs])
         _check(lib.twist_aggregate(self.h, plan.h, arr, len(subs), C.byref(full.c)), self.h)
 
+    def twist_aggregate_image_bytes(self) -> int:
+        n = _sz()
+        _check(lib.twist_aggregate_image_bytes(self.h, C.byref(n)), self.h)
+        return n.value
+
+    def twist_aggregate_begin(self, plan: "Plan", image: torch.Tensor | None = None) -> "Accum":
+        if image is None:
+            image = torch.empty(self.twist_aggregate_image_bytes(), dtype=torch.uint8, device="cuda")
+        h = _vp()
+        _check(lib.twist_aggregate_begin(self.h, plan.h, _vp(image.data_ptr()), image.numel(), C.byref(h)), self.h)
+        return Accum(self, plan, h, image)
+
+    def _round_desc(self, S, heads_sub, ffn_units_sub, B, N, local_steps, seed, rnd, opt, layer_shared, scale_mode):
+        keep = []
+        ls = None
+        if layer_shared is not None:
+            ls = (C.c_uint8 * self.desc.n_layers)(*[int(bool(x)) for x in layer_shared])
+            keep.append(ls)
+        sd = SampleDesc(S, heads_sub, ffn_units_sub, None, 0, None, 0, ls, 1, scale_mode, seed, rnd)
+        od = OptDesc(opt.get("kind", OPT_SGD), opt.get("lr", 1e-2), opt.get("beta1", 0.9), opt.get("beta2", 0.999), opt.get("eps", 1e-8),
+                     opt.get("weight_decay", 0.0))
+        return RoundDesc(sd, od, local_steps, B, N), keep
+
+    def twist_round_bytes(self, S, heads_sub, ffn_units_sub, B, N, local_steps=1, seed=0, rnd=0, opt=None, layer_shared=None,
+                          scale_mode=SCALE_SQRT_RATIO):
+        """(subnet_bytes, workspace_bytes, image_bytes) of twist_round with these arguments."""
+        rd, _keep = self._round_desc(S, heads_sub, ffn_units_sub, B, N, local_steps, seed, rnd, opt or {}, layer_shared, scale_mode)
+        a, b, c = _sz(), _sz(), _sz()
+        _check(lib.twist_round_bytes(self.h, C.byref(rd), C.byref(a), C.byref(b), C.byref(c)), self.h)
+        return a.value, b.value, c.value
+
+    def twist_round(self, full: "FullWeights", inputs: torch.Tensor, targets: torch.Tensor, S, heads_sub, ffn_units_sub, subnet_storage,
+                    workspace, image, loss, seed=0, rnd=0, opt=None, layer_shared=None, scale_mode=SCALE_SQRT_RATIO) -> None:
+        """inputs/targets [S, local_steps, B, N(, d_model)]; loss fp32 [S, local_steps] (device)."""
+        local_steps, B, N = inputs.shape[1], inputs.shape[2], inputs.shape[3]
+        rd, _keep = self._round_desc(S, heads_sub, ffn_units_sub, B, N, local_steps, seed, rnd, opt or {}, layer_shared, scale_mode)
+        _check(lib.twist_round(self.h, C.byref(rd), C.byref(full.c), _vp(inputs.data_ptr()), _vp(targets.data_ptr()),
+                               _vp(subnet_storage.data_ptr()), subnet_storage.numel(), _vp(workspace.data_ptr()), workspace.numel(),
+                               _vp(image.data_ptr()), image.numel(), _vp(loss.data_ptr())), self.h)
+
 
     def twist_gemm_raw(self, layout: int, M: int, N: int, K: int, A: torch.Tensor, B: torch.Tensor, out: torch.Tensor, alpha: float = 1.0) -> None:
         """out[M,N] = alpha * op(A) op(B); layouts as in include/twist.h; row strides taken from the tensors."""
@@ -236,6 +287,26 @@ class Plan:
     def close(self):
         if getattr(self, "h", None):
             lib.twist_plan_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+
+class Accum:
+    """twist_aggregate_begin / add / finish / destroy: the aggregation one subnet at a time."""
+
+    def __init__(self, ctx: Context, plan: "Plan", h, image: torch.Tensor):
+        self.ctx, self.plan, self.h, self.image = ctx, plan, h, image
+
+    def twist_aggregate_add(self, sub: "Subnet") -> None:
+        _check(lib.twist_aggregate_add(self.h, sub.h), self.ctx.h)
+
+    def twist_aggregate_finish(self, full: "FullWeights") -> None:
+        _check(lib.twist_aggregate_finish(self.h, C.byref(full.c)), self.ctx.h)
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.twist_aggregate_destroy(self.h)
             self.h = None
 
     __del__ = close

@@ -507,6 +507,185 @@ extern "C" twist_status twist_aggregate(twist_ctx *ctx, const twist_plan *plan, 
   return for_each_group(ctx, plan, inout, 0, true, ml, [&](const MoveLaunch &m, int blocks) { return twist_launch_aggregate(ctx, m, blocks); });
 }
 
+// ------------------------------------------------------------------------------------------------ running-sum aggregate
+struct twist_accum {
+  twist_ctx *ctx = nullptr;
+  const twist_plan *plan = nullptr;
+  float *base = nullptr;
+  std::vector<int64_t> layer_off;                 // [n_layers * TWIST_N_LAYER_TENSORS] element offsets, -1 = absent
+  int64_t global_off[TWIST_N_GLOBAL_TENSORS];
+  int32_t rows[TWIST_MAX_S];                      // blueprint rows added so far, in order
+  int32_t n_rows = 0;
+};
+
+namespace {
+
+// Offsets of every central tensor inside the fp32 image (each tensor starts on a 256-byte boundary); returns the
+// image's size in elements.
+int64_t image_layout(const twist_model_desc &d, std::vector<int64_t> *layer_off, int64_t *global_off) {
+  int64_t n = 0;
+  int r, c;
+  if (layer_off) layer_off->assign((size_t)d.n_layers * TWIST_N_LAYER_TENSORS, -1);
+  for (int l = 0; l < d.n_layers; ++l)
+    for (int t = 0; t < TWIST_N_LAYER_TENSORS; ++t) {
+      if (!layer_tensor_present(d, t)) continue;
+      full_shape(d, t, r, c);
+      if (layer_off) (*layer_off)[(size_t)l * TWIST_N_LAYER_TENSORS + t] = n;
+      n += (int64_t)align_up((size_t)r * c, 64);
+    }
+  for (int t = 0; t < TWIST_N_GLOBAL_TENSORS; ++t) {
+    if (global_off) global_off[t] = -1;
+    if (!global_tensor_present(d, t)) continue;
+    global_shape(d, t, r, c);
+    if (global_off) global_off[t] = n;
+    n += (int64_t)align_up((size_t)r * c, 64);
+  }
+  return n;
+}
+
+// One launch per layer (and one for the model-level tensors) over the central layout.  `full` is null for an add.
+twist_status for_each_image_group(twist_accum *acc, const twist_full_weights *full, MoveLaunch &ml, bool finish) {
+  twist_ctx *ctx = acc->ctx;
+  const twist_model_desc &d = ctx->d;
+  const int VN = 16 / ctx->esize();
+  for (int l = -1; l < d.n_layers; ++l) {
+    const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
+    ml.n_jobs = 0;
+    int64_t blocks = 0;
+    for (int t = 0; t < nt; ++t) {
+      const int64_t off = l < 0 ? acc->global_off[t] : acc->layer_off[(size_t)l * TWIST_N_LAYER_TENSORS + t];
+      if (off < 0) continue;
+      float *img = acc->base + off;
+      const void *fp = finish ? (l < 0 ? full->global_tensors[t] : full->layer_tensors[(size_t)l * TWIST_N_LAYER_TENSORS + t]) : img;
+      MoveJob &jb = ml.job[ml.n_jobs];
+      if (!make_job(ctx, acc->plan, l, t, fp, 0, true, ml.n_subs, jb)) continue;
+      if (jb.vec) jb.vec = 1;
+      jb.acc = img;
+      const int64_t total = (int64_t)jb.rows * jb.n_full * (jb.vec ? jb.Q / VN : jb.Q);
+      if (total >= (int64_t)1 << 31) TW_FAIL(ctx, TWIST_ESHAPE, "running-sum aggregate: a tensor of %lld vectors exceeds the 32-bit index range", (long long)total);
+      jb.blk_begin = (int32_t)blocks;
+      blocks += (total + kAccumPerBlock - 1) / kAccumPerBlock;
+      ++ml.n_jobs;
+    }
+    TW_TRY(twist_launch_accumulate(ctx, ml, (int)blocks, finish));
+  }
+  return TWIST_OK;
+}
+
+}  // namespace
+
+extern "C" twist_status twist_aggregate_image_bytes(twist_ctx *ctx, size_t *bytes) {
+  if (!ctx || !bytes) TW_FAIL(ctx, TWIST_EINVAL, "twist_aggregate_image_bytes: null argument");
+  *bytes = (size_t)image_layout(ctx->d, nullptr, nullptr) * sizeof(float);
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_aggregate_begin(twist_ctx *ctx, const twist_plan *plan, void *image, size_t image_bytes, twist_accum **out) {
+  if (!ctx || !plan || !image || !out) TW_FAIL(ctx, TWIST_EINVAL, "twist_aggregate_begin: null argument");
+  if (plan->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_aggregate_begin: plan belongs to another context");
+  if (reinterpret_cast<uintptr_t>(image) % 256) TW_FAIL(ctx, TWIST_ESHAPE, "twist_aggregate_begin: image must be 256-byte aligned");
+  twist_accum *acc = new (std::nothrow) twist_accum;
+  if (!acc) TW_FAIL(ctx, TWIST_ENOMEM, "twist_aggregate_begin: out of host memory");
+  acc->ctx = ctx; acc->plan = plan; acc->base = static_cast<float *>(image);
+  const size_t need = (size_t)image_layout(ctx->d, &acc->layer_off, acc->global_off) * sizeof(float);
+  if (image_bytes < need) {
+    delete acc;
+    TW_FAIL(ctx, TWIST_ESHAPE, "twist_aggregate_begin: image of %zu bytes is smaller than the %zu needed", image_bytes, need);
+  }
+  *out = acc;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_aggregate_add(twist_accum *acc, const twist_subnet *sub) {
+  if (!acc || !sub) TW_FAIL(acc ? acc->ctx : nullptr, TWIST_EINVAL, "twist_aggregate_add: null argument");
+  twist_ctx *ctx = acc->ctx;
+  if (sub->plan != acc->plan) TW_FAIL(ctx, TWIST_EINVAL, "twist_aggregate_add: subnet was not extracted from this plan");
+  for (int i = 0; i < acc->n_rows; ++i)
+    if (acc->rows[i] == sub->s) TW_FAIL(ctx, TWIST_EINVAL, "twist_aggregate_add: blueprint row %d added twice", sub->s);
+  MoveLaunch ml;
+  std::memset(&ml, 0, sizeof ml);
+  ml.n_subs = acc->n_rows + 1;
+  ml.sub_base[0] = sub->params;
+  ml.sub_row[0] = sub->s;
+  for (int i = 0; i < acc->n_rows; ++i) ml.sub_row[1 + i] = acc->rows[i];
+  TW_TRY(for_each_image_group(acc, nullptr, ml, false));
+  acc->rows[acc->n_rows++] = sub->s;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_aggregate_finish(twist_accum *acc, const twist_full_weights *inout) {
+  if (!acc) TW_FAIL(nullptr, TWIST_EINVAL, "twist_aggregate_finish: null argument");
+  twist_ctx *ctx = acc->ctx;
+  TW_TRY(check_full(ctx, inout, "twist_aggregate_finish"));
+  if (acc->n_rows == 0) return TWIST_OK;  // nothing reported: the central model stays
+  MoveLaunch ml;
+  std::memset(&ml, 0, sizeof ml);
+  ml.n_subs = acc->n_rows;
+  for (int i = 0; i < acc->n_rows; ++i) ml.sub_row[i] = acc->rows[i];
+  TW_TRY(for_each_image_group(acc, inout, ml, true));
+  acc->n_rows = 0;
+  return TWIST_OK;
+}
+
+extern "C" void twist_aggregate_destroy(twist_accum *acc) { delete acc; }
+
+// ------------------------------------------------------------------------------------------------ one whole round
+namespace {
+size_t batch_elems(const twist_ctx *ctx, int B, int N) { return (size_t)B * N * (ctx->d.vocab > 0 ? 1 : ctx->d.d_model); }
+size_t batch_esize(const twist_ctx *ctx) { return ctx->d.vocab > 0 ? sizeof(int32_t) : (size_t)ctx->esize(); }
+int store_of(const twist_opt_desc &o) { return o.kind == TWIST_OPT_ADAMW ? TWIST_STORE_ADAMW : TWIST_STORE_GRADS; }
+}  // namespace
+
+extern "C" twist_status twist_round_bytes(twist_ctx *ctx, const twist_round_desc *rd, size_t *subnet_bytes, size_t *workspace_bytes,
+                                          size_t *image_bytes) {
+  if (!ctx || !rd || !subnet_bytes || !workspace_bytes || !image_bytes) TW_FAIL(ctx, TWIST_EINVAL, "twist_round_bytes: null argument");
+  twist_plan *plan = nullptr;
+  TW_TRY(twist_sample(ctx, &rd->sample, &plan));  // sizes depend on the widths only, not on the draw
+  size_t sb = 0, wb = 0, ib = 0;
+  twist_status st = twist_subnet_bytes(ctx, plan, store_of(rd->opt), &sb);
+  if (st == TWIST_OK) {
+    twist_subnet probe;
+    probe.ctx = ctx; probe.plan = plan;
+    st = twist_train_workspace_bytes(ctx, &probe, rd->B, rd->N, &wb);
+  }
+  if (st == TWIST_OK) st = twist_aggregate_image_bytes(ctx, &ib);
+  twist_plan_destroy(plan);
+  if (st != TWIST_OK) return st;
+  *subnet_bytes = sb; *workspace_bytes = wb; *image_bytes = ib;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_round(twist_ctx *ctx, const twist_round_desc *rd, const twist_full_weights *inout, const void *inputs,
+                                    const void *targets, void *subnet_storage, size_t subnet_bytes, void *workspace, size_t workspace_bytes,
+                                    void *image, size_t image_bytes, float *loss_dev) {
+  if (!ctx || !rd || !inputs || !targets || !subnet_storage || !workspace || !image || !loss_dev) TW_FAIL(ctx, TWIST_EINVAL, "twist_round: null argument");
+  if (rd->local_steps < 1) TW_FAIL(ctx, TWIST_EINVAL, "twist_round: local_steps=%d must be at least 1", rd->local_steps);
+  TW_TRY(check_full(ctx, inout, "twist_round"));
+  twist_plan *plan = nullptr;
+  TW_TRY(twist_sample(ctx, &rd->sample, &plan));
+  twist_accum *acc = nullptr;
+  twist_status st = twist_aggregate_begin(ctx, plan, image, image_bytes, &acc);
+  const size_t step_bytes = batch_elems(ctx, rd->B, rd->N) * batch_esize(ctx);
+  for (int s = 0; st == TWIST_OK && s < plan->S; ++s) {
+    twist_subnet *sub = nullptr;
+    st = twist_extract(ctx, plan, inout, s, subnet_storage, subnet_bytes, store_of(rd->opt), &sub);
+    for (int j = 0; st == TWIST_OK && j < rd->local_steps; ++j) {
+      const size_t b = (size_t)s * rd->local_steps + j;
+      st = twist_train_fwd_bwd(ctx, sub, static_cast<const char *>(inputs) + b * step_bytes, static_cast<const char *>(targets) + b * step_bytes,
+                               rd->B, rd->N, workspace, workspace_bytes, loss_dev + b);
+      if (st == TWIST_OK) st = twist_train_step(ctx, sub, &rd->opt);
+    }
+    if (st == TWIST_OK) st = twist_aggregate_add(acc, sub);
+    twist_subnet_destroy(sub);
+  }
+  if (st == TWIST_OK) st = twist_aggregate_finish(acc, inout);
+  // the plan's device tables are read by kernels still in flight: drain the stream before releasing them
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess && st == TWIST_OK) st = TWIST_EHIP;
+  twist_aggregate_destroy(acc);
+  twist_plan_destroy(plan);
+  return st;
+}
+
 // ------------------------------------------------------------------------------------------------ training entry points
 extern "C" twist_status twist_workspace_bytes(twist_ctx *ctx, const twist_subnet *sub, int32_t B, int32_t N, size_t *bytes) {
   if (!ctx || !sub || !bytes) TW_FAIL(ctx, TWIST_EINVAL, "twist_workspace_bytes: null argument");

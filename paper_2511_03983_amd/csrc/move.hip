@@ -17,6 +17,7 @@ namespace {
 constexpr int kThreads = 256;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int ES> struct VecOf;
 template <> struct VecOf<2> { using vec = u32x4; using elem = uint16_t; static constexpr int N = 8; };
@@ -471,6 +472,94 @@ __global__ __launch_bounds__(kThreads) void aggregate_rows_kernel(const MoveLaun
   pull_rows<ES, TU>(ml, jb, blockIdx.x - jb.blk_begin);
 }
 
+// ------------------------------------------------------------------------------------------- running-sum aggregate
+// The aggregation formula of Section 3.3 evaluated one subnet at a time, so that only one subnet has to be resident:
+// an fp32 image of the central model receives each subnet's values (stored by the first owner of a block, added by
+// later ones, which makes clearing the image unnecessary), and the last pass divides by the number of owners and
+// rounds once.  The additions happen in the order of the calls, so the result is bit-identical to the one-shot pull
+// over the same subnets in the same order.
+template <int ES, int VN, bool FINISH>
+__device__ __forceinline__ void accumulate_body(const MoveLaunch &ml, const MoveJob &jb, uint32_t lb) {
+  using E = typename VecOf<ES>::elem;
+  constexpr int TU = kAccumPerBlock / kThreads;
+  const uint32_t q = jb.Q / VN, Wf = (uint32_t)jb.n_full * q, Ws = (uint32_t)jb.n_sub * q;
+  const uint32_t total = (uint32_t)jb.rows * Wf;
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const uint32_t f = lb * (uint32_t)kAccumPerBlock + u * kThreads + threadIdx.x;
+    if (f >= total) continue;
+    const uint32_t row = f / Wf, v = f - row * Wf;
+    const uint32_t unit = v / q, j = v - unit * q;
+    float *a = jb.acc + (int64_t)f * VN;
+    float x[VN];
+    if (!FINISH) {
+      const int p = jb.table ? jb.table[(int64_t)ml.sub_row[0] * jb.n_full + unit] : 0;
+      if (p < 0) continue;
+      bool first = true;
+      for (int i = 1; i < ml.n_subs; ++i) first = first && jb.table && jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] < 0;
+      const E *sp = reinterpret_cast<const E *>(ml.sub_base[0] + jb.sub_off * ES) + ((int64_t)row * Ws + (int64_t)p * q + j) * VN;
+      if (VN > 1) {
+        const u32x4 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(sp));
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < VN; ++i) x[i] = ES == 2 ? bf16_to_f32((w[i / 2] >> (16 * (i & 1))) & 0xffff) : __uint_as_float(w[i % 4]);
+      } else {
+        x[0] = elem_to_f32<ES>(*sp);
+      }
+      if (VN > 1) {
+        f32x4 *a4 = reinterpret_cast<f32x4 *>(a);  // the image is 256-byte aligned and f * VN a multiple of 4
+#pragma unroll
+        for (int h = 0; h < VN / 4; ++h) {
+          f32x4 t = {x[4 * h % VN], x[(4 * h + 1) % VN], x[(4 * h + 2) % VN], x[(4 * h + 3) % VN]};
+          if (!first) t = a4[h] + t;
+          a4[h] = t;
+        }
+      } else {
+        a[0] = first ? x[0] : a[0] + x[0];
+      }
+    } else {
+      int cnt = 0;
+      for (int i = 0; i < ml.n_subs; ++i) cnt += !jb.table || jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] >= 0;
+      if (cnt == 0) continue;  // no owner: the central values stay
+      const float c = (float)cnt;
+      E *out = reinterpret_cast<E *>(const_cast<void *>(jb.full)) + (int64_t)f * VN;
+      if (VN > 1) {
+        const f32x4 *a4 = reinterpret_cast<const f32x4 *>(a);
+#pragma unroll
+        for (int h = 0; h < VN / 4; ++h) {
+          const f32x4 t = a4[h];
+          x[4 * h % VN] = t.x / c; x[(4 * h + 1) % VN] = t.y / c; x[(4 * h + 2) % VN] = t.z / c; x[(4 * h + 3) % VN] = t.w / c;
+        }
+      } else {
+        x[0] = a[0] / c;
+      }
+      if (VN > 1) {
+        u32x4 o;
+        if (ES == 2) {
+          o.x = f32_to_bf16(x[0]) | (f32_to_bf16(x[1 % VN]) << 16);
+          o.y = f32_to_bf16(x[2 % VN]) | (f32_to_bf16(x[3 % VN]) << 16);
+          o.z = f32_to_bf16(x[4 % VN]) | (f32_to_bf16(x[5 % VN]) << 16);
+          o.w = f32_to_bf16(x[6 % VN]) | (f32_to_bf16(x[7 % VN]) << 16);
+        } else {
+          o.x = __float_as_uint(x[0]); o.y = __float_as_uint(x[1 % VN]); o.z = __float_as_uint(x[2 % VN]); o.w = __float_as_uint(x[3 % VN]);
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(out));
+      } else {
+        *out = f32_to_elem<ES>(x[0]);
+      }
+    }
+  }
+}
+
+template <int ES, bool FINISH>
+__global__ __launch_bounds__(kThreads) void accumulate_kernel(const MoveLaunch ml) {
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  const uint32_t lb = blockIdx.x - jb.blk_begin;
+  if (jb.vec) accumulate_body<ES, VecOf<ES>::N, FINISH>(ml, jb, lb);
+  else accumulate_body<ES, 1, FINISH>(ml, jb, lb);
+}
+
 // ------------------------------------------------------------------------------------------- helpers
 template <int ES>
 __global__ __launch_bounds__(kThreads) void to_f32_kernel(const void *src, float *dst, int64_t n) {
@@ -504,6 +593,20 @@ twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int to
     else hipLaunchKernelGGL((aggregate_rows_kernel<4, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   } else if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   else hipLaunchKernelGGL(aggregate_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_launch_accumulate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks, bool finish) {
+  if (total_blocks <= 0) return TWIST_OK;
+  const dim3 g(total_blocks), b(kThreads);
+  if (ctx->esize() == 2) {
+    if (finish) hipLaunchKernelGGL((accumulate_kernel<2, true>), g, b, 0, ctx->stream, ml);
+    else hipLaunchKernelGGL((accumulate_kernel<2, false>), g, b, 0, ctx->stream, ml);
+  } else {
+    if (finish) hipLaunchKernelGGL((accumulate_kernel<4, true>), g, b, 0, ctx->stream, ml);
+    else hipLaunchKernelGGL((accumulate_kernel<4, false>), g, b, 0, ctx->stream, ml);
+  }
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }

@@ -112,6 +112,7 @@ struct MoveJob {
   int32_t vec;                // 0 = element path, 1 = 16-byte path, 2 = 16-byte row-block path (segments of whole
                               //     multiples of 256 vectors, one row, at most 8 subnets)
   int32_t blk_begin;          // first workgroup of this job inside the launch
+  float *acc;                 // running-sum aggregate only: fp32 image of the central tensor [rows][n_full*Q]
 };
 
 #define TWIST_MAX_JOBS 20
@@ -125,6 +126,10 @@ struct MoveLaunch {
 
 twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
 twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
+// Running-sum aggregate: add subnet sub_base[0] (blueprint row sub_row[0]; rows sub_row[1..n_subs) were added before it)
+// into the fp32 image, or (finish) write image / owner count over all rows sub_row[0..n_subs) to the central tensors.
+constexpr int kAccumPerBlock = 256 * 4;  // vectors (or elements) of the central tensor one workgroup covers
+twist_status twist_launch_accumulate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks, bool finish);
 // fp32 master <- weights, zero-fill helpers
 twist_status twist_launch_to_f32(twist_ctx *ctx, const void *src, float *dst, int64_t n);
 twist_status twist_launch_zero(twist_ctx *ctx, void *dst, size_t bytes);

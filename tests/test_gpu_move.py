@@ -158,6 +158,50 @@ def test_aggregate_matches_formula(lib, name, drop):
         assert rel_fro(got["globals"][k], w) <= tol
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("drop", [False, True])
+def test_running_sum_aggregate_equals_the_one_shot_aggregate_bit_for_bit(lib, name, drop):
+    """twist_aggregate_begin/add/finish with one subnet resident at a time, against twist_aggregate over all of them."""
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=11)
+    other_t = to_device(full_np, cfg)
+    fw2 = lib.FullWeights(other_t["layers"], other_t["globals"])
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    for s, sub in enumerate(subs):
+        _perturb(cfg, sub, s)
+    use = list(range(S))
+    if drop:
+        use = (use[1:] if S > 1 else use)[::-1]
+    ctx.twist_aggregate(plan, [subs[s] for s in use], fw)
+    image = torch.full((ctx.twist_aggregate_image_bytes() // 4,), float("nan"), device="cuda").view(torch.uint8)   # need not be cleared
+    acc = ctx.twist_aggregate_begin(plan, image)
+    slab = torch.empty(ctx.twist_subnet_bytes(plan), dtype=torch.uint8, device="cuda")      # ONE subnet's storage, reused
+    for s in use:
+        one = ctx.twist_extract(plan, fw2, s, storage=slab)      # re-create subnet s in the shared slab ...
+        slab.copy_(subs[s].storage)                               # ... with its trained values
+        acc.twist_aggregate_add(one)
+        with pytest.raises(lib.TwistError):
+            acc.twist_aggregate_add(one)                          # a blueprint row reports once
+    acc.twist_aggregate_finish(fw2)
+    for l in range(cfg.n_layers):
+        for k in full_t["layers"][l]:
+            assert torch.equal(full_t["layers"][l][k].view(torch.uint8), other_t["layers"][l][k].view(torch.uint8)), (name, l, k)
+    for k in full_t["globals"]:
+        assert torch.equal(full_t["globals"][k].view(torch.uint8), other_t["globals"][k].view(torch.uint8)), (name, k)
+    # independent of the one-shot kernel: the formula itself, on the tensors of the last layer
+    sub_np = {s: subnet_to_numpy(subs[s], cfg) for s in use}
+    want = omove.aggregate(full_np, oplan, sub_np, cfg.d_head, cfg.ffn_granule)
+    got = model_to_numpy(other_t, cfg)
+    tol = 5e-3 if cfg.dtype == "bf16" else 1e-4
+    for k, w in want["layers"][-1].items():
+        assert rel_fro(got["layers"][-1][k], w) <= tol, (name, k)
+    # finish forgot the added rows: the same object serves another pass, and nothing added leaves the model alone
+    before = {k: v.clone() for k, v in other_t["layers"][0].items()}
+    acc.twist_aggregate_finish(fw2)
+    for k, v in before.items():
+        assert torch.equal(v.view(torch.uint8), other_t["layers"][0][k].view(torch.uint8)), k
+    acc.close()
+
+
 def test_untrained_partition_roundtrip_is_bit_exact(lib):
     cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "gpt_bf16", seed=6)     # 12 = 4*3 heads, 3072 = 4*768
     before = model_to_numpy(full_t, cfg)

@@ -186,6 +186,61 @@ def test_local_steps_then_aggregate(lib, name, opt):
         assert rel_fro(to_numpy(full_t["globals"][k]), w) <= tol, k
 
 
+@pytest.mark.parametrize("name,opt", [("gpt_f32", "sgd"), ("llama_f32_um", "sgd"), ("llama_bf16", "adamw")])
+def test_rounds_on_a_persistent_central_model_match_the_checker(lib, name, opt):
+    """twist_round x 3: resample, train each subnet on its own batches for the repartition interval, aggregate; the
+    central model carries over from round to round (Section 3; Section 5 resamples every few batches)."""
+    cfg, S, hs, fs, B, N = CASES[name]
+    bf = cfg.dtype == "bf16"
+    hook = _round_hook if bf else (lambda t, a: a)
+    k_steps, rounds, seed = 2, 3, 21
+    lr = 1e-2 if opt == "sgd" else 1e-4
+    optd = {"kind": lib.OPT_SGD if opt == "sgd" else lib.OPT_ADAMW, "lr": lr, "weight_decay": 0.01}
+    full_np = si.make_weights(cfg, 2, std=0.05 if not bf else 0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    sb, wb, ib = ctx.twist_round_bytes(S, hs, fs, B, N, k_steps, opt=optd)
+    slab, ws, image = (torch.empty(n, dtype=torch.uint8, device="cuda") for n in (sb, wb, ib))
+    losses = torch.zeros(S, k_steps, device="cuda")
+    central = full_np
+    for r in range(rounds):
+        batches = [[_data(cfg, B, N, 1000 * r + 10 * s + j) for j in range(k_steps)] for s in range(S)]
+        x = torch.stack([torch.stack([b[2] for b in row]) for row in batches])
+        y = torch.stack([torch.stack([b[3] for b in row]) for row in batches])
+        ctx.twist_round(fw, x, y, S, hs, fs, slab, ws, image, losses, seed=seed, rnd=r, opt=optd)
+        # the checker's round
+        oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, seed, rnd=r)
+        osubs, olosses = [], np.zeros((S, k_steps))
+        for s in range(S):
+            osub = omove.extract(central, oplan, s, cfg.d_head, cfg.ffn_granule)
+            master = {"layers": [dict(lw) for lw in osub["layers"]], "globals": dict(osub["globals"])}
+            state = ooptim.adamw_init(master)
+            for j in range(k_steps):
+                olosses[s, j], og = omodel.forward_backward(cfg, osub, batches[s][j][0], batches[s][j][1], q=hook)
+                og = {"layers": og["layers"], "globals": og["globals"]}
+                if opt == "sgd":
+                    ooptim.sgd_step(master, og, lr)
+                else:
+                    ooptim.adamw_step(master, og, state, lr=lr, weight_decay=0.01)
+                osub = {"layers": [{k: (si.to_bf16_grid(v) if bf else v) for k, v in lw.items()} for lw in master["layers"]],
+                        "globals": {k: (si.to_bf16_grid(v) if bf else v) for k, v in master["globals"].items()}}
+            osubs.append(osub)
+        central = omove.aggregate(central, oplan, osubs, cfg.d_head, cfg.ffn_granule)
+        if bf:
+            central = {"layers": [{k: si.to_bf16_grid(v) for k, v in lw.items()} for lw in central["layers"]],
+                       "globals": {k: si.to_bf16_grid(v) for k, v in central["globals"].items()}}
+        tol = 5e-3 if bf else 1e-4
+        np.testing.assert_allclose(losses.cpu().numpy(), olosses, rtol=tol)
+        for l in range(cfg.n_layers):
+            for k, w in central["layers"][l].items():
+                assert rel_fro(_stored(cfg, k, to_numpy(full_t["layers"][l][k])), w) <= tol, (r, l, k)
+        for k, w in central["globals"].items():
+            assert rel_fro(to_numpy(full_t["globals"][k]), w) <= tol, (r, k)
+    # the weights moved: three rounds of training are not a no-op
+    assert rel_fro(to_numpy(full_t["globals"]["tok_embed"]), full_np["globals"]["tok_embed"]) > 0
+
+
 def test_scale_mode_none_and_shape_errors(lib):
     cfg, S, hs, fs, B, N = CASES["gpt_f32"]
     full_np = si.make_weights(cfg, 1, std=0.05, generic=True)
