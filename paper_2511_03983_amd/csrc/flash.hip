@@ -428,6 +428,33 @@ __device__ __forceinline__ bf16x8 frag_tr(const char *rows, uint32_t a, uint32_t
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// Loads from global memory straight into LDS (lane l writes its 16 or 4 bytes at lds + bytes * l; lanes whose offset
+// is outside the descriptor's range write zeros).  Written as assembly on purpose: for the builtin form the compiler
+// cannot tell which LDS bytes a load fills and makes every later transposing LDS read wait for ALL such loads in
+// flight, which turns the prefetch of the next tile into a stall.  Completion is awaited explicitly (DL_WAIT_VM0
+// followed by a barrier) before any wave reads the bytes.  M0 (the LDS base of the instruction) is saved and restored.
+typedef uint32_t desc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ desc_t make_desc(const void *p, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(p);
+  desc_t d;
+  d.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  d.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+  d.z = __builtin_amdgcn_readfirstlane(bytes);
+  d.w = 0x00020000u;
+  return d;
+}
+template <int BYTES>
+__device__ __forceinline__ void dma(desc_t desc, const char *lds, uint32_t voff) {
+  const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void)(lds));
+  uint32_t keep;
+  if (BYTES == 16)
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "s"(l), "v"(voff), "s"(desc) : "memory");
+  else
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dword %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "s"(l), "v"(voff), "s"(desc) : "memory");
+}
+
 // Each of the 4 waves brings in 4 of the 16 one-KB pieces (4 rows each) of a tile.
 struct TileLoader {
   uint32_t off[4];  // byte offset of this lane's chunk within tile 0, from the buffer base
@@ -438,10 +465,9 @@ struct TileLoader {
       off[i] = (uint32_t)(row * ld_elems * 2) + col_byte0 + chunk * 16;
     }
   }
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, char *dst, uint32_t tile_byte0, int wave) const {
+  __device__ __forceinline__ void issue(desc_t rsrc, char *dst, uint32_t tile_byte0, int wave) const {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void)(dst + (wave + 4 * i) * 1024), 16, off[i] + tile_byte0, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) dma<16>(rsrc, dst + (wave + 4 * i) * 1024, off[i] + tile_byte0);
   }
 };
 
@@ -460,7 +486,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
   const uint16_t *qp = batch + (int64_t)h * DH;
   const int q0 = qb * 128 + wave * 32, q = q0 + c;
   const float sc = scale * kLog2e;
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(batch, (uint32_t)(N * ld * 2));
+  const desc_t rs = make_desc(batch, (uint32_t)(N * ld * 2));
   const uint32_t tstep = (uint32_t)(64 * ld * 2);
   TileLoader lk, lv;
   lk.init(ld, (uint32_t)((HD + h * DH) * 2), wave, lane);
@@ -585,7 +611,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
   const int q0 = qb * 128 + wave * 32, q = q0 + c;
   const float sc = scale * kLog2e;
   const float L2 = lse[((int64_t)b * Hs + h) * N + q] * kLog2e;
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(batch, (uint32_t)(N * ld * 2));
+  const desc_t rs = make_desc(batch, (uint32_t)(N * ld * 2));
   const uint32_t tstep = (uint32_t)(64 * ld * 2);
   TileLoader lk, lv;
   lk.init(ld, (uint32_t)((HD + h * DH) * 2), wave, lane);
@@ -683,8 +709,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
   const int k0 = kb * 128 + wave * 32, kv = k0 + c;
   const float sc = scale * kLog2e;
   const float *lse_b = lse + ((int64_t)b * Hs + h) * N, *del_b = delta + ((int64_t)b * Hs + h) * N;
-  const __amdgpu_buffer_rsrc_t rq = make_rsrc(batch, (uint32_t)(N * ld * 2)), rg = make_rsrc(gbatch, (uint32_t)(N * HD * 2));
-  const __amdgpu_buffer_rsrc_t rl = make_rsrc(lse_b, (uint32_t)(N * 4)), rd = make_rsrc(del_b, (uint32_t)(N * 4));
+  const desc_t rq = make_desc(batch, (uint32_t)(N * ld * 2)), rg = make_desc(gbatch, (uint32_t)(N * HD * 2));
+  const desc_t rl = make_desc(lse_b, (uint32_t)(N * 4)), rd = make_desc(del_b, (uint32_t)(N * 4));
   const uint32_t qstep = (uint32_t)(64 * ld * 2), gstep = (uint32_t)(64 * HD * 2);
   TileLoader lq, lg;
   lq.init(ld, (uint32_t)(h * DH * 2), wave, lane);
@@ -696,8 +722,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
     lq.issue(rq, smem + st * STAGE_B, (uint32_t)qt * qstep, wave);
     lg.issue(rg, smem + st * STAGE_B + TILE_B, (uint32_t)qt * gstep, wave);
     // the tile's 64 log-sum-exps and deltas: one 4-byte-per-lane load each, by waves 0 and 1
-    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rl, (lds_void)(smem + 2 * STAGE_B + st * 512), 4, (uint32_t)((qt * 64 + lane) * 4), 0, 0, 0);
-    if (wave == 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (lds_void)(smem + 2 * STAGE_B + st * 512 + 256), 4, (uint32_t)((qt * 64 + lane) * 4), 0, 0, 0);
+    if (wave == 0) dma<4>(rl, smem + 2 * STAGE_B + st * 512, (uint32_t)((qt * 64 + lane) * 4));
+    if (wave == 1) dma<4>(rd, smem + 2 * STAGE_B + st * 512 + 256, (uint32_t)((qt * 64 + lane) * 4));
   };
   issue(qt0, 0);
 
@@ -722,16 +748,33 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
     const char *Qt = smem + ST * STAGE_B, *Gt = Qt + TILE_B;
     const float *Ls = reinterpret_cast<const float *>(smem + 2 * STAGE_B + ST * 512), *Ds = Ls + 64;
     const bool diag = qt * 64 < k0 + 31;
+    // LDS latency is far longer than one matrix instruction, so every fragment is requested well before its use:
+    // the 16 row fragments of a 32-query half-tile before the score products, the 16 transposed fragments while
+    // the softmax arithmetic runs, and the next half-tile's row fragments under the dK/dV products.
+    bf16x8 qf[KS], gf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) { qf[ks] = frag(Qt, ro.fo[ks]); gf[ks] = frag(Gt, ro.fo[ks]); }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        s = MFMA(frag(Qt + mt * 8192, ro.fo[ks]), kf[ks], s);
-        dp = MFMA(frag(Gt + mt * 8192, ro.fo[ks]), vf[ks], dp);
+        s = MFMA(qf[ks], kf[ks], s);
+        dp = MFMA(gf[ks], vf[ks], dp);
       }
+      bf16x8 tg[2][MT], tq[2][MT];
+      auto load_tr = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          tg[t][i] = frag_tr(Gt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]);
+          tq[t][i] = frag_tr(Qt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]);
+        }
+      };
+      load_tr(0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int qrow = mt * 32 + 8 * r4 + 4 * g;  // first of 4 consecutive query rows inside the tile
@@ -746,14 +789,24 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
           s[r] = p;
         }
       }
+      const bf16x8 pf0 = pack8(s, 0), df0 = pack8(dp, 0), pf1 = pack8(s, 8), df1 = pack8(dp, 8);
+      __builtin_amdgcn_sched_barrier(0);
+      load_tr(1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 pf = pack8(s, 8 * t), df = pack8(dp, 8 * t);
+      for (int i = 0; i < MT; ++i) {
+        dv[i] = MFMA(tg[0][i], pf0, dv[i]);
+        dk[i] = MFMA(tq[0][i], df0, dk[i]);
+      }
+      if (mt == 0) {
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
-          dv[i] = MFMA(frag_tr(Gt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), pf, dv[i]);
-          dk[i] = MFMA(frag_tr(Qt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]), df, dk[i]);
-        }
+        for (int ks = 0; ks < KS; ++ks) { qf[ks] = frag(Qt + 8192, ro.fo[ks]); gf[ks] = frag(Gt + 8192, ro.fo[ks]); }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        dv[i] = MFMA(tg[1][i], pf1, dv[i]);
+        dk[i] = MFMA(tq[1][i], df1, dk[i]);
       }
     }
   };
