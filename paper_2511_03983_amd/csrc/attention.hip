@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_plain(const void *qkv, const
 
 twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, bool *done);
 twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                      void *dqkv, int B, int N, int Hs, int dh, bool *done);
+                                      void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab, bool *done, bool *rope_done);
 
 twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
@@ -188,14 +188,14 @@ twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void
 }
 
 twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                 void *dqkv, int B, int N, int Hs, int dh) {
+                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)(((int64_t)B * Hs * N + 3) / 4)), block(256);
   if (bf16) {
-    bool done = false;
-    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, dh, &done));
-    if (done) return TWIST_OK;
+    bool done = false, rope_done = false;
+    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, dh, rope_tab, &done, &rope_done));
+    if (done) return (rope_tab && !rope_done) ? twist_rope_apply(ctx, bf16, dqkv, rope_tab, B, N, Hs, dh, -1.f) : TWIST_OK;
   }
   if (bf16) {
     hipLaunchKernelGGL(attn_bwd_dq_plain<1>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
@@ -205,7 +205,7 @@ twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, cons
     hipLaunchKernelGGL(attn_bwd_dkv_plain<0>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
   }
   TW_HIP(ctx, hipGetLastError());
-  return TWIST_OK;
+  return rope_tab ? twist_rope_apply(ctx, bf16, dqkv, rope_tab, B, N, Hs, dh, -1.f) : TWIST_OK;
 }
 
 extern "C" twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs, void *o, float *o32,
@@ -216,7 +216,7 @@ extern "C" twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, con
   TW_TRY(twist_attention_fwd(ctx, bf, qkv, o, o32, lse, B, N, Hs, ctx->d.d_head));
   if (dout) {
     if (!delta || !dqkv) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: backward needs delta and dqkv");
-    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head));
+    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head, nullptr));
   }
   return TWIST_OK;
 }

@@ -597,8 +597,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
   if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
 }
 
+// Backward of the rotary embedding on a lane's 64 gradient values of one row (acc[i][4 j + e] is head-dim column
+// 32 i + 8 j + 4 g + e): columns f and f + 64 form a pair rotated by the angle of (position, f); the backward pass turns
+// the gradient by the opposite angle.  tab holds (cos, sin) for f = 0..63 of every position, 128 floats per position.
+__device__ __forceinline__ void rope_grad(f32x16 (&acc)[MT], const float *tab, int pos, int g) {
+  const f32x4 *row = reinterpret_cast<const f32x4 *>(tab + (int64_t)pos * DH);
+#pragma unroll
+  for (int i = 0; i < MT / 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int f = 32 * i + 8 * j + 4 * g;  // first of the lane's four consecutive pair indices
+      const f32x4 w0 = row[f / 2], w1 = row[f / 2 + 1];
+      const float cs[4] = {w0[0], w0[2], w1[0], w1[2]}, sn[4] = {w0[1], w0[3], w1[1], w1[3]};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a = acc[i][4 * j + e], b = acc[i + MT / 2][4 * j + e];
+        acc[i][4 * j + e] = a * cs[e] + b * sn[e];
+        acc[i + MT / 2][4 * j + e] = b * cs[e] - a * sn[e];
+      }
+    }
+}
+
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_bwd_dq_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
-                                                              uint16_t *dqkv, int N, int Hs, float scale) {
+                                                              uint16_t *dqkv, int N, int Hs, float scale, const float *rope) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
   const int nqb = N / 128, nbh = gridDim.x / nqb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -684,6 +705,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     step(kt, std::integral_constant<int, 0>());
     step(kt + 1, std::integral_constant<int, 1>());
   }
+  if (rope) rope_grad(acc, rope, q, g);
   uint16_t *op = dqkv + ((int64_t)b * N + q) * ld + (int64_t)h * DH;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -695,7 +717,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 }
 
 __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
-                                                               uint16_t *dqkv, int N, int Hs, float scale) {
+                                                               uint16_t *dqkv, int N, int Hs, float scale, const float *rope) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 2 * 512];  // + per stage: 64 log-sum-exps, 64 deltas
   const int nkb = N / 128, nbh = gridDim.x / nkb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -814,6 +836,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
     step(qt, std::integral_constant<int, 0>());
     step(qt + 1, std::integral_constant<int, 1>());
   }
+  if (rope) rope_grad(dk, rope, kv, g);
   uint16_t *op = dqkv + ((int64_t)b * N + kv) * ld + (int64_t)h * DH;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -858,17 +881,20 @@ twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, 
 }
 
 twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta, void *dqkv,
-                                      int B, int N, int Hs, int dh, bool *done) {
+                                      int B, int N, int Hs, int dh, const float *rope_tab, bool *done, bool *rope_done) {
   static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
   *done = false;
+  *rope_done = false;
   if (off || !o32 || !shape_ok(qkv, dout, N, Hs, dh) || (reinterpret_cast<uintptr_t>(dqkv) % 16) || (reinterpret_cast<uintptr_t>(o32) % 16)) return TWIST_OK;
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv), *gout = static_cast<const uint16_t *>(dout);
   uint16_t *dx = static_cast<uint16_t *>(dqkv);
   if (dh == 128 && dl_ok(B, N, Hs, dh)) {
-    hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
-    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    const float *rt = rope_tab && (reinterpret_cast<uintptr_t>(rope_tab) % 16) == 0 ? rope_tab : nullptr;
+    hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, rt);
+    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, rt);
+    *rope_done = rt != nullptr;
   } else if (dh == 128) {
     hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
     hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);

@@ -26,9 +26,11 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
 // o32 (may be null): the same output unrounded, [T, Hs*dh] fp32, written by the tiled bf16 kernels only; the
 // tiled backward kernels need it (without it, or on shapes they do not cover, the plain kernels run).
 twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh);
-// dqkv [T, 3*Hs*dh] from do [T, Hs*dh]; delta [B,Hs,N] fp32 scratch (sum_j p_ij dp_ij, written by the dq pass)
+// dqkv [T, 3*Hs*dh] from do [T, Hs*dh]; delta [B,Hs,N] fp32 scratch (sum_j p_ij dp_ij, written by the dq pass).
+// rope_tab (may be null): the table of twist_rope_table; when given, the q and k gradients are also taken back through
+// the rotary embedding (inside the tiled kernels where they cover the shape, else by twist_rope_apply afterwards).
 twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                 void *dqkv, int B, int N, int Hs, int dh);
+                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab);
 
 twist_status twist_embed_fwd(twist_ctx *ctx, int bf16, const int32_t *tok, const void *tok_embed, const void *pos_embed, float *x, int B, int N, int D, int vocab);
 twist_status twist_embed_bwd(twist_ctx *ctx, const int32_t *tok, const float *dx, float *d_tok, float *d_pos, int B, int N, int D);
@@ -38,10 +40,17 @@ twist_status twist_cast_in(twist_ctx *ctx, int bf16, const void *src, float *dst
 // y = norm(x) * w (+ b); stats[2*T] = (mean or 0, rstd) per row
 twist_status twist_norm_fwd(twist_ctx *ctx, int bf16, int rms, const float *x, const void *w, const void *b, void *y, float *stats, int T, int D, float eps);
 // dx (+)= norm backward of dy; dxb = activation-type copy of the resulting dx (may be null);
-// dw, db (fp32, overwritten; db may be null); partial: scratch of at least norm_partial_floats(T, D)
+// dw, db (fp32, overwritten; db may be null); partial: scratch of at least norm_partial_floats(T, D).
+// With defer_reduce the per-chunk partial sums are left in `partial` and dw/db are not written: the caller later sums
+// many such buffers with one twist_norm_reduce_batch launch (same summation order, hence the same bits).
 twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
-                            int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D);
+                            int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D, bool defer_reduce = false);
 size_t twist_norm_partial_floats(int T, int D);
+struct NormReduce {
+  const float *partial;
+  float *dw, *db;  // db may be null
+};
+twist_status twist_norm_reduce_batch(twist_ctx *ctx, const NormReduce *items, int n, int T, int D);
 
 // column sums: out[n] = alpha * sum_t src[t, n] (fp32, overwritten); partial scratch >= colsum_partial_floats
 twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int Ncols);

@@ -256,6 +256,35 @@ __global__ __launch_bounds__(kT) void reduce_partial_kernel(const float *partial
   }
 }
 
+// the same reduction for a batch of norm layers in one launch: blockIdx.y = layer, and both parameter gradients
+constexpr int kReduceBatch = 64;
+struct NormReduceArgs {
+  NormReduce item[kReduceBatch];
+};
+__global__ __launch_bounds__(kT) void reduce_partial_batch_kernel(const NormReduceArgs a, int n_chunks, int D) {
+  __shared__ float sh[16][16];
+  const NormReduce it = a.item[blockIdx.y];
+  const int col = threadIdx.x & 15, slice = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + col;
+  for (int which = 0; which < 2; ++which) {
+    float *out = which ? it.db : it.dw;
+    if (!out) continue;  // uniform over the workgroup
+    const float *partial = it.partial + which * D;
+    float s = 0.f;
+    if (c < D)
+      for (int k = slice; k < n_chunks; k += 16) s += partial[(int64_t)k * 2 * D + c];
+    __syncthreads();
+    sh[slice][col] = s;
+    __syncthreads();
+    if (slice == 0 && c < D) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) t += sh[i][col];
+      out[c] = 1.f * t;
+    }
+  }
+}
+
 template <int BF>
 __global__ __launch_bounds__(64) void colsum_kernel(const void *src, int64_t ld, float *partial, int T, int n) {
   const int c = blockIdx.x * 64 + threadIdx.x;
@@ -630,7 +659,7 @@ size_t twist_norm_partial_floats(int T, int D) { return (size_t)n_chunks(T) * 2 
 size_t twist_colsum_partial_floats(int T, int n) { return (size_t)n_chunks(T) * n; }
 
 twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
-                            int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D) {
+                            int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D, bool defer_reduce) {
   const int nc = n_chunks(T);
   const int nv = D % 256 == 0 ? D / 256 : 0;
   const bool fused_ok = al16(dy) && al16(x) && al16(w) && al16(dx) && (!dxb || al16(dxb)) && (nv == 1 || nv == 2 || nv == 3 || nv == 4 || nv == 8 || (nv == 16 && rms && bf16));
@@ -654,6 +683,7 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
     }
 #undef TW_NORM_FUSED
     TW_HIP(ctx, hipGetLastError());
+    if (defer_reduce) return TWIST_OK;
     hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
     if (db) hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
     TW_HIP(ctx, hipGetLastError());
@@ -661,13 +691,25 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
   }
   // general shapes: parameter gradients first (they read dy and x, which the dx pass leaves untouched)
   LAUNCH_BF(norm_bwd_dw_kernel, bf16, dim3((D + 63) / 64, nc), dim3(64), dy, x, stats, partial, T, D);
-  hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
+  if (!defer_reduce) hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)2 * D, nc, 1.f, dw, D);
   TW_HIP(ctx, hipGetLastError());
-  if (db) {
+  if (db && !defer_reduce) {
     hipLaunchKernelGGL(reduce_partial_kernel, dim3((D + 15) / 16), dim3(kT), 0, ctx->stream, partial + D, (int64_t)2 * D, nc, 1.f, db, D);
     TW_HIP(ctx, hipGetLastError());
   }
   LAUNCH_BF2(norm_bwd_dx_kernel, bf16, rms, dim3((T + 3) / 4), dim3(kT), dy, x, w, stats, dx, accumulate, dxb, T, D);
+  return TWIST_OK;
+}
+
+twist_status twist_norm_reduce_batch(twist_ctx *ctx, const NormReduce *items, int n, int T, int D) {
+  const int nc = n_chunks(T);
+  for (int i0 = 0; i0 < n; i0 += kReduceBatch) {
+    NormReduceArgs a;
+    const int m = std::min(kReduceBatch, n - i0);
+    for (int i = 0; i < m; ++i) a.item[i] = items[i0 + i];
+    hipLaunchKernelGGL(reduce_partial_batch_kernel, dim3((D + 15) / 16, m), dim3(kT), 0, ctx->stream, a, nc, D);
+    TW_HIP(ctx, hipGetLastError());
+  }
   return TWIST_OK;
 }
 

@@ -33,6 +33,8 @@ struct Workspace {
   std::vector<float *> stats; // (mean, rstd) per row for each norm
   std::vector<LayerBufs> layer;
   float *dx, *rope_tab, *rowloss, *partial, *delta;
+  float *norm_partial;  // one block of per-chunk norm-gradient sums per norm layer (2 n_layers + 1), reduced in one launch at the end
+  size_t norm_partial_stride;
   void *dxb, *dxb2, *hf, *logits, *da, *dgu, *dh, *dout, *dqkv;
   int64_t ld_logits;
   size_t bytes;
@@ -74,6 +76,8 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
   w.rope_tab = c.take<float>((size_t)N * d.d_head * 4);
   const size_t widest = std::max({D, 3 * hd_max, (size_t)nf * f_max});
   w.partial = c.take<float>(std::max(twist_norm_partial_floats((int)T, (int)D), twist_colsum_partial_floats((int)T, (int)widest)) * 4);
+  w.norm_partial_stride = align_up(twist_norm_partial_floats((int)T, (int)D), 64);
+  w.norm_partial = c.take<float>(w.norm_partial_stride * (2 * (size_t)d.n_layers + 1) * 4);
   w.delta = c.take<float>((size_t)B * h_max * N * 4);
   w.da = c.take(T * f_max * es);
   w.dgu = c.take(T * nf * f_max * es);
@@ -186,6 +190,15 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     e.alpha = alpha; e.bias = bias; e.residual = residual; e.out = out; e.out_f32 = out_f32;
     return twist_gemm(ctx, bf, lay, M, Nn, K, A, lda, Bm, ldb, ldc, e);
   };
+  // Norm backward of norm layer `idx` (2l, 2l+1: the two norms of layer l; 2 n_layers: the final norm).  Its parameter
+  // gradients are left as per-chunk partial sums in the layer's own block and summed for all layers by one launch at
+  // the end of the pass, which takes 2 n_layers small kernels off the chain of dependent kernels.
+  std::vector<NormReduce> norm_items;
+  auto norm_bwd = [&](int idx, const void *dy, const float *x, const void *nw, int accumulate, void *dxb, float *dw, float *db) {
+    float *part = w.norm_partial + (size_t)idx * w.norm_partial_stride;
+    norm_items.push_back({part, dw, db});
+    return twist_norm_bwd(ctx, bf, rms, dy, x, nw, w.stats[idx], w.dx, accumulate, dxb, dw, db, part, T, D, true);
+  };
 
   // ------------------------------------------------------------------------------------ forward
   if (lm) {
@@ -230,8 +243,8 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     // projection weight gradient, then the gradient flowing back into the final norm
     TW_TRY(gemm(GEMM_TN, V, D, T, w.logits, w.ld_logits, w.hf, D, G(wout), D, 1));
     TW_TRY(gemm(GEMM_NN, T, D, V, w.logits, w.ld_logits, P(wout), D, w.dh, D, 0));
-    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, x_last, P(L.global[TWIST_FINAL_NORM_W]), w.stats[2 * d.n_layers], w.dx, 0, w.dxb,
-                          G(L.global[TWIST_FINAL_NORM_W]), G(L.global[TWIST_FINAL_NORM_B]), w.partial, T, D));
+    TW_TRY(norm_bwd(2 * d.n_layers, w.dh, x_last, P(L.global[TWIST_FINAL_NORM_W]), 0, w.dxb, G(L.global[TWIST_FINAL_NORM_W]),
+                    G(L.global[TWIST_FINAL_NORM_B])));
   } else {
     TW_TRY(twist_mse_fwd_bwd(ctx, bf, x_last, targets, w.dx, w.dxb, w.rowloss, loss_dev, (int64_t)T * D));
     if (forward_only) return TWIST_OK;
@@ -269,8 +282,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.done(1));
     TW_TRY(gemm(GEMM_NN, T, D, nf * F, w.dgu, nf * F, P(w1), D, w.dh, D, 0));
     TW_TRY(side.wait_done(2));
-    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), w.stats[2 * l + 1], w.dx, 1, gx_other, G(L.at(l, TWIST_NORM2_W)),
-                          G(L.at(l, TWIST_NORM2_B)), w.partial, T, D));
+    TW_TRY(norm_bwd(2 * l + 1, w.dh, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), 1, gx_other, G(L.at(l, TWIST_NORM2_W)), G(L.at(l, TWIST_NORM2_B))));
     // attention branch: y = c_a (o C_attn^T + b_o)
     if (L.at(l, TWIST_BO).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx_other, D, c_a, G(L.at(l, TWIST_BO)), w.partial, T, D));
     TW_TRY(side.fork(2));
@@ -281,17 +293,16 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     else TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
     TW_TRY(mask(w.dout, l, TWIST_KIND_HEAD, dh));
     TW_TRY(side.wait_done(3));
-    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh));
-    if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, w.dqkv, w.rope_tab, B, N, Hs, dh, -1.f));
+    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh, d.use_rope ? w.rope_tab : nullptr));
     if (L.at(l, TWIST_BQ).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dqkv, 3 * HD, 1.f, G(L.at(l, TWIST_BQ)), w.partial, T, 3 * HD));
     TW_TRY(side.fork(3));
     TW_TRY(wgrad(3 * HD, D, w.dqkv, 3 * HD, b.h1, D, G(L.at(l, TWIST_WQ)), 1.f));
     TW_TRY(side.done(3));
     TW_TRY(gemm(GEMM_NN, T, D, 3 * HD, w.dqkv, 3 * HD, P(L.at(l, TWIST_WQ)), D, w.dh, D, 0));
     TW_TRY(side.wait_done(0));
-    TW_TRY(twist_norm_bwd(ctx, bf, rms, w.dh, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), w.stats[2 * l], w.dx, 1, gx, G(L.at(l, TWIST_NORM1_W)),
-                          G(L.at(l, TWIST_NORM1_B)), w.partial, T, D));
+    TW_TRY(norm_bwd(2 * l, w.dh, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), 1, gx, G(L.at(l, TWIST_NORM1_W)), G(L.at(l, TWIST_NORM1_B))));
   }
+  TW_TRY(twist_norm_reduce_batch(ctx, norm_items.data(), (int)norm_items.size(), T, D));
   for (int i = 0; i < 4; ++i) TW_TRY(side.wait_done(i));  // join: the caller's stream sees the whole pass
   (void)gx_other;
 
