@@ -475,6 +475,54 @@ __device__ __forceinline__ u32x4v pack8(const F8 &f) {
   return u;
 }
 
+// Cross-entropy of a bf16 row of at most NV * 2048 logits held in registers: one read of the row, one write of its
+// gradient (the general kernel above walks the row three times with 2-byte accesses).  ld8 = row stride / 8; columns
+// between V and the stride are padding and get zeros.
+template <int NV>
+__global__ __launch_bounds__(kT) void ce_vec_kernel(u32x4v *logits, int64_t ld8, const int32_t *targets, float *rowloss, int V, float inv_T) {
+  __shared__ float sh[4];
+  u32x4v *row = logits + (int64_t)blockIdx.x * ld8;
+  F8 x[NV];
+  float m = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int idx = k * kT + threadIdx.x;
+    if (idx < ld8) {
+      x[k] = unpack8(row[idx]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (idx * 8 + e >= V) x[k].v[e] = -INFINITY;
+        m = fmaxf(m, x[k].v[e]);
+      }
+    }
+  }
+  m = block_max(m, sh);
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k)
+    if (k * kT + (int)threadIdx.x < ld8) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += __expf(x[k].v[e] - m);
+    }
+  s = block_sum(s, sh);
+  const float lse = m + logf(s);
+  const int tgt = targets[blockIdx.x];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int idx = k * kT + threadIdx.x;
+    if (idx < ld8) {
+      F8 g;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = idx * 8 + e;
+        if (c == tgt) rowloss[blockIdx.x] = lse - x[k].v[e];
+        g.v[e] = c < V ? (__expf(x[k].v[e] - lse) - (c == tgt ? 1.f : 0.f)) * inv_T : 0.f;
+      }
+      row[idx] = pack8(g);
+    }
+  }
+}
+
 // a = silu(g) * u on [T, 2F] (gate | up) -> [T, F]; i8 runs over T * F/8
 __global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u32x4v *a, int F8n, int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
@@ -765,7 +813,12 @@ twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, co
 }
 
 twist_status twist_ce_fwd_bwd(twist_ctx *ctx, int bf16, void *logits, int64_t ld, const int32_t *targets, float *rowloss, float *loss, int T, int V) {
-  LAUNCH_BF(ce_kernel, bf16, dim3(T), dim3(kT), logits, ld, targets, rowloss, V, 1.f / (float)T);
+  if (bf16 && ld % 8 == 0 && ld <= 16 * 2048 && al16(logits)) {
+    u32x4v *lv = static_cast<u32x4v *>(logits);
+    if (ld <= 4 * 2048) hipLaunchKernelGGL(ce_vec_kernel<4>, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
+    else hipLaunchKernelGGL(ce_vec_kernel<16>, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
+  } else
+    LAUNCH_BF(ce_kernel, bf16, dim3(T), dim3(kT), logits, ld, targets, rowloss, V, 1.f / (float)T);
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kT), 0, ctx->stream, rowloss, (int64_t)T, 1.f / (float)T, loss);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
