@@ -281,6 +281,61 @@ def bench_golden_ticket(args, tw, si, torch):
     return res
 
 
+def bench_clock_under_load(tw, si, torch):
+    """Shader clock reported by rocm-smi while the projection kernel runs back to back on the whole chip (8192^3, about
+    3 s), next to the idle reading: the published MFMA peak assumes the 2.4 GHz boost clock, the chip holds less under
+    this load.  Best effort: None when rocm-smi is missing or prints something else."""
+    import re
+    import subprocess
+    import threading
+
+    def sclk():
+        try:
+            r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
+            m = re.search(r"sclk clock level: \S+ \((\d+)Mhz\)", r.stdout)
+            return int(m.group(1)) if m else None
+        except Exception:
+            return None
+
+    idle = sclk()
+    if idle is None:
+        return None
+    ctx = tw.Context(tw.desc_from_cfg(si.CFG3))
+    g = torch.Generator(device="cuda").manual_seed(1)
+    n = 8192
+    a = torch.randn(n, n, device="cuda", generator=g).bfloat16()
+    b = torch.randn(n, n, device="cuda", generator=g).bfloat16()
+    c = torch.empty(n, n, device="cuda", dtype=torch.bfloat16)
+    samples = []
+
+    def sampler():
+        time.sleep(1.5)
+        for _ in range(2):
+            samples.append(sclk())
+            time.sleep(0.4)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0, launches = time.time(), 0
+    e0.record()
+    while time.time() - t0 < 3.0:
+        for _ in range(50):
+            ctx.twist_gemm_raw(0, n, n, n, a, b, c)
+        torch.cuda.synchronize()
+        launches += 50
+    e1.record()
+    torch.cuda.synchronize()
+    th.join()
+    samples = [x for x in samples if x]
+    if not samples:
+        return None
+    mhz = sum(samples) / len(samples)
+    tf = 2.0 * n ** 3 * launches / e0.elapsed_time(e1) / 1e9
+    return {"before_mhz": idle, "projection_load_mhz": mhz, "projection_8192_cubed_tflops": tf,
+            "mfma_peak_at_that_clock_tflops": PEAK_BF16_TFLOPS * mhz / 2400.0, "frac_of_peak_at_that_clock": tf / (PEAK_BF16_TFLOPS * mhz / 2400.0)}
+
+
 def bench_latency_ablation(args, tw, si, torch):
     """Latency study of Section 5 (Figure 4 / Table 2) on synthetic data: GPT-2-small shape, blocks = heads and
     d_ff/12-neuron FFN blocks, first and last two layers shared, kept blocks kappa in {10, 8, 6, 4} of 12 for the
@@ -379,6 +434,8 @@ def main():
     log("[bench] movers ([out, in] output projections):", json.dumps(movers_rm))
     golden = None if args.skip_golden else bench_golden_ticket(args, tw, si, torch)
     log("[bench] golden ticket (7B shape, pruned vs unpruned):", json.dumps(golden))
+    clock = None if args.skip_movers else bench_clock_under_load(tw, si, torch)
+    log("[bench] clock under projection load:", json.dumps(clock))
     ablation = bench_latency_ablation(args, tw, si, torch) if args.ablation else None
     if ablation:
         log("[bench] latency ablation (GPT-2-small shape):", json.dumps(ablation))
@@ -416,6 +473,8 @@ def main():
             "traffic_unit": "bytes per layer (8 extract launches + 1 aggregate launch) behind the L2",
             "algorithmic_bytes_per_layer": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) * 1e9 / 32}
         out["movers_llama7b_stack_out_in_layout"] = movers_rm
+    if clock:
+        out["clock_under_projection_load"] = clock
     if golden:
         out["golden_ticket_llama7b_fwd_bwd"] = golden
     if ablation:
