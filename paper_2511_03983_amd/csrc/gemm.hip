@@ -355,9 +355,12 @@ struct Frags {
   }
 };
 
-template <int AKM, int BKM>
+// SPLIT: the k range is cut into `ksplit` parts of `kchunk` (a multiple of 32) and a work item is (part, tile); part p
+// writes its unscaled fp32 partial product to ep.out + p * M * ldc and splitk_reduce_kernel adds the parts.  Used for
+// products with few output tiles and a long k (weight gradients), which would otherwise occupy a fraction of the CUs.
+template <int AKM, int BKM, bool SPLIT>
 __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, Ep ep,
-                                                      int tiles_m, int tiles_n) {
+                                                      int tiles_m, int tiles_n, int ksplit, int kchunk) {
   constexpr int TM = 2, TN = 4;
   constexpr int EPI_LD = 136;                    // floats per staged output row: 4 rows apart = 32 banks apart
   constexpr int EPI_WAVE = 32 * EPI_LD * 4;      // one wave's 32 x 128 block of fp32 results
@@ -374,9 +377,13 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
   // Persistent workgroups: each walks the tiles vid, vid + gridDim.x, ...; the stores of one tile drain while the
   // next tile's loads are already under way.  Tile numbers are dealt so that each of the 8 XCDs (own L2; workgroup
   // b runs on XCD b % 8) works on a contiguous range of tiles.
-  for (int vid = blockIdx.x; vid < nb; vid += gridDim.x) {
-  int bid = vid;
+  const int n_items = SPLIT ? nb * ksplit : nb;
+  for (int vid = blockIdx.x; vid < n_items; vid += gridDim.x) {
+  const int part = SPLIT ? vid / nb : 0;
+  int bid = SPLIT ? vid - part * nb : vid;
   if (nb % 8 == 0) bid = (bid % 8) * (nb / 8) + bid / 8;
+  const int kbeg = SPLIT ? part * kchunk : 0;
+  const int Kl = SPLIT ? min(kchunk, K - kbeg) : K;  // this item's k extent
   constexpr int GROUP = 8;
   const int per_group = GROUP * tiles_n;
   const int grp = bid / per_group, first_m = grp * GROUP;
@@ -394,14 +401,14 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
 
   Loader<AKM> la;
   Loader<BKM> lb;
-  la.init(AKM ? A + (int64_t)m0 * lda : A + m0, lda, M - m0, K, wave, lane);
-  lb.init(BKM ? B + (int64_t)n0 * ldb : B + n0, ldb, N - n0, K, wave, lane);
+  la.init(AKM ? A + (int64_t)m0 * lda + kbeg : A + (int64_t)kbeg * lda + m0, lda, M - m0, Kl, wave, lane);
+  lb.init(BKM ? B + (int64_t)n0 * ldb + kbeg : B + (int64_t)kbeg * ldb + n0, ldb, N - n0, Kl, wave, lane);
 
-  const int nsub = (K + SK - 1) / SK;
+  const int nsub = (Kl + SK - 1) / SK;
 #pragma unroll
   for (int u = 0; u < NST - 1; ++u) {
-    la.issue(u, K, smem + u * STG, wave);
-    lb.issue(u, K, smem + u * STG + OPB, wave);
+    la.issue(u, Kl, smem + u * STG, wave);
+    lb.issue(u, Kl, smem + u * STG + OPB, wave);
   }
   PP_WAIT_VM8_LGKM0;  // sub-tile 0 has landed (4 loads per sub-tile and wave)
   __builtin_amdgcn_s_barrier();
@@ -420,8 +427,8 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
 #pragma unroll
       for (int j = 0; j < TN; ++j) bfr[ks][j] = fb.get(sb, j, ks);
     }
-    la.issue(u + NST - 1, K, dn, wave);
-    lb.issue(u + NST - 1, K, dn + OPB, wave);
+    la.issue(u + NST - 1, Kl, dn, wave);
+    lb.issue(u + NST - 1, Kl, dn + OPB, wave);
     PP_WAIT_VM8_LGKM0;  // own fragments are in registers; own loads of sub-tile u + 1 have landed
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
@@ -446,6 +453,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
   float *stage = reinterpret_cast<float *>(smem + wave * EPI_WAVE);
   const int c = lane & 31, g = lane >> 5;
   const int rows_left = M - m0;
+  void *const outp = SPLIT ? static_cast<void *>(static_cast<float *>(ep.out) + (int64_t)part * M * ep.ldc) : ep.out;
   const int ncol = n0 + wn + 4 * c;  // first of this lane's 4 columns
   float bias[4] = {0.f, 0.f, 0.f, 0.f};
   if (ep.bias) {
@@ -477,10 +485,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
         }
         if (ep.out_f32) {
           const f32x4 w = {v[0], v[1], v[2], v[3]};
-          *reinterpret_cast<f32x4 *>(static_cast<float *>(ep.out) + o) = w;
+          *reinterpret_cast<f32x4 *>(static_cast<float *>(outp) + o) = w;
         } else {
           const u32x2 w = {(uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16)};
-          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(ep.out) + o) = w;
+          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outp) + o) = w;
         }
       } else {
 #pragma unroll
@@ -488,8 +496,8 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
           if (ncol + e >= N) break;
           float x = v[e];
           if (ep.residual) x += ep.residual[o + e];
-          if (ep.out_f32) static_cast<float *>(ep.out)[o + e] = x;
-          else static_cast<uint16_t *>(ep.out)[o + e] = f2bf(x);
+          if (ep.out_f32) static_cast<float *>(outp)[o + e] = x;
+          else static_cast<uint16_t *>(outp)[o + e] = f2bf(x);
         }
       }
     }
@@ -501,6 +509,39 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
 
 }  // namespace pp
 
+// out = alpha * sum over parts of the fp32 partial products [parts][M][N] (parts added in ascending order)
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int parts, int M, int N, void *out, int64_t ldc, int out_f32, float alpha) {
+  const int64_t total = (int64_t)M * N, i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= total) return;
+  const bool vec = N % 4 == 0 && ldc % 4 == 0;  // then a group of 4 lies in one row and is 16-byte aligned
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < parts; ++p) {
+    const float *src = ws + (int64_t)p * total + i;
+    if (vec) {
+      const f32x4 t = *reinterpret_cast<const f32x4 *>(src);
+      v[0] += t[0]; v[1] += t[1]; v[2] += t[2]; v[3] += t[3];
+    } else {
+      for (int e = 0; e < 4 && i + e < total; ++e) v[e] += src[e];
+    }
+  }
+  for (int e = 0; e < 4 && i + e < total; ++e) {
+    const int64_t m = (i + e) / N, n = (i + e) - m * N, o = m * ldc + n;
+    if (out_f32) static_cast<float *>(out)[o] = alpha * v[e];
+    else static_cast<uint16_t *>(out)[o] = f2bf(alpha * v[e]);
+  }
+}
+
+// number of k parts for a product with few 256x256 output tiles and a long k (1 = do not split)
+int choose_ksplit(int M, int N, int K, int *kchunk) {
+  const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  *kchunk = K;
+  if (tiles >= 128 || K < 1024) return 1;
+  int ks = std::min({16, 256 / tiles, K / 512});
+  if (ks < 2) return 1;
+  *kchunk = ((K + ks - 1) / ks + 31) / 32 * 32;
+  return (K + *kchunk - 1) / *kchunk;
+}
+
 template <int AKM, int BKM>
 void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
   // the 256x256 ping-pong kernel (one persistent workgroup per CU) from 64 tiles up, else 128x128 tiles (4 waves of 64x64)
@@ -509,7 +550,7 @@ void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t
   const bool use_big = force ? atoi(force) == 256 : big >= 64;
   if (use_big) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
-    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM>), dim3(std::min(tm * tn, 256)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
+    hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM, false>), dim3(std::min(tm * tn, 256)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn, 1, K);
   } else {
     const int tm = (M + 127) / 128, tn = (N + 127) / 128;
     hipLaunchKernelGGL((gemm_mfma_kernel<AKM, BKM, 128, 128, 2, 2>), dim3(tm * tn), dim3(256), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn);
@@ -550,6 +591,23 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   const bool vec_ok = bf16 && !no_mfma && aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0 && k_ok && span_ok;
   if (vec_ok) {
     const uint16_t *a = static_cast<const uint16_t *>(A), *b = static_cast<const uint16_t *>(B);
+    int kchunk = K;
+    const int ks = (e.splitk_ws && !e.bias && !e.residual && !getenv("TWIST_GEMM_TILE")) ? choose_ksplit(M, N, K, &kchunk) : 1;
+    if (ks > 1 && (size_t)ks * M * N <= e.splitk_floats && aligned16(e.splitk_ws)) {
+      const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+      Ep part{1.f, nullptr, nullptr, e.splitk_ws, 1, N, N % 4 == 0};
+      const dim3 grid(std::min(tm * tn * ks, 256)), block(512);
+      switch (lay) {
+        case GEMM_NT: hipLaunchKernelGGL((pp::gemm_pp_kernel<1, 1, true>), grid, block, 0, stream, M, N, K, a, lda, b, ldb, part, tm, tn, ks, kchunk); break;
+        case GEMM_NN: hipLaunchKernelGGL((pp::gemm_pp_kernel<1, 0, true>), grid, block, 0, stream, M, N, K, a, lda, b, ldb, part, tm, tn, ks, kchunk); break;
+        case GEMM_TN: hipLaunchKernelGGL((pp::gemm_pp_kernel<0, 0, true>), grid, block, 0, stream, M, N, K, a, lda, b, ldb, part, tm, tn, ks, kchunk); break;
+      }
+      TW_HIP(ctx, hipGetLastError());
+      const int64_t groups = ((int64_t)M * N + 3) / 4;
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream, e.splitk_ws, ks, M, N, e.out, ldc, e.out_f32, e.alpha);
+      TW_HIP(ctx, hipGetLastError());
+      return TWIST_OK;
+    }
     switch (lay) {
       case GEMM_NT: launch_mfma<1, 1>(stream, M, N, K, a, lda, b, ldb, ep); break;
       case GEMM_NN: launch_mfma<1, 0>(stream, M, N, K, a, lda, b, ldb, ep); break;

@@ -9,7 +9,13 @@ struct GemmEpilogue {
   const float *residual = nullptr;  // [M,N] fp32
   void *out = nullptr;           // [M,N]
   int out_f32 = 0;               // 1: out is fp32, 0: out is the activation type
+  // Optional scratch for products with few output tiles and a long contraction (weight gradients): when given (and no
+  // bias/residual is asked for) the contraction may be cut into parts whose fp32 partial products go here and are then
+  // summed in a fixed order.  At most 256 tiles of 256 x 256 floats are ever needed.
+  float *splitk_ws = nullptr;
+  size_t splitk_floats = 0;
 };
+constexpr size_t kSplitkFloats = (size_t)256 * 256 * 256;
 
 enum GemmLayout {
   GEMM_NT = 0,  // A [M,K] row-major, B [N,K] row-major         (y = x W^T)

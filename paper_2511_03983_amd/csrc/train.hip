@@ -33,6 +33,7 @@ struct Workspace {
   std::vector<float *> stats; // (mean, rstd) per row for each norm
   std::vector<LayerBufs> layer;
   float *dx, *rope_tab, *rowloss, *partial, *delta;
+  float *splitk;        // scratch of the weight-gradient projections that are cut along the token dimension
   float *norm_partial;  // one block of per-chunk norm-gradient sums per norm layer (2 n_layers + 1), reduced in one launch at the end
   size_t norm_partial_stride;
   void *dxb, *dxb2, *hf, *logits, *da, *dgu, *dh, *dout, *dqkv;
@@ -76,6 +77,7 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
   w.rope_tab = c.take<float>((size_t)N * d.d_head * 4);
   const size_t widest = std::max({D, 3 * hd_max, (size_t)nf * f_max});
   w.partial = c.take<float>(std::max(twist_norm_partial_floats((int)T, (int)D), twist_colsum_partial_floats((int)T, (int)widest)) * 4);
+  w.splitk = c.take<float>(kSplitkFloats * 4);
   w.norm_partial_stride = align_up(twist_norm_partial_floats((int)T, (int)D), 64);
   w.norm_partial = c.take<float>(w.norm_partial_stride * (2 * (size_t)d.n_layers + 1) * 4);
   w.delta = c.take<float>((size_t)B * h_max * N * 4);
@@ -256,6 +258,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   auto wgrad = [&](int M, int Nn, const void *A, int64_t lda, const void *Bm, int64_t ldb, float *out, float alpha) {
     GemmEpilogue e;
     e.alpha = alpha; e.out = out; e.out_f32 = 1;
+    e.splitk_ws = w.splitk; e.splitk_floats = kSplitkFloats;  // one scratch: these projections are serialised on their stream
     return twist_gemm(ctx, bf, GEMM_TN, M, Nn, T, A, lda, Bm, ldb, Nn, e, side.stream());
   };
   void *gx = w.dxb, *gx_other = w.dxb2;  // gradient of the residual stream in activation type: current, spare

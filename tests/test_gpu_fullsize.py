@@ -117,3 +117,17 @@ def test_second_stream_weight_gradients_are_bit_identical_to_serial_schedule(lib
             else:
                 assert torch.equal(g, other[1][key]), key
             assert torch.isfinite(g).all() and float(g.abs().max()) > 0.0, key
+    # The weight gradients above were computed with the token dimension cut into parts (few output tiles, 8192 tokens).
+    # The same pass with that disabled (every projection on the 256x256-tile kernel, one contraction) must agree to
+    # fp32 summation-order accuracy.
+    import os
+    os.environ["TWIST_GEMM_TILE"] = "256"
+    try:
+        ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["TWIST_GEMM_TILE"]
+    for l in range(cfg.n_layers):
+        for k in ("wq", "wo", "w_gate", "w_down"):
+            g0, g1 = results[0][1][(l, k)], sub.twist_subnet_view(l, k, 1)
+            assert float((g0 - g1).norm() / g1.norm()) <= 1e-5, (l, k)
