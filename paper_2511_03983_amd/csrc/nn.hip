@@ -523,6 +523,43 @@ __global__ __launch_bounds__(kT) void ce_vec_kernel(u32x4v *logits, int64_t ld8,
   }
 }
 
+// The same for rows of any length (row stride a multiple of 8): one vectorised pass keeps a running maximum and a
+// sum of exponentials relative to it, a second pass re-reads the row (it is still in the L2) and writes the gradient.
+__global__ __launch_bounds__(kT) void ce_vec_long_kernel(u32x4v *logits, int64_t ld8, const int32_t *targets, float *rowloss, int V, float inv_T) {
+  __shared__ float sh[4];
+  u32x4v *row = logits + (int64_t)blockIdx.x * ld8;
+  float m = -INFINITY, s = 0.f;
+  for (int idx = threadIdx.x; idx < ld8; idx += kT) {
+    const F8 x = unpack8(row[idx]);
+    float mx = m;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (idx * 8 + e < V) mx = fmaxf(mx, x.v[e]);
+    if (mx == -INFINITY) continue;  // nothing but padding so far
+    float t = s * __expf(m - mx);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (idx * 8 + e < V) t += __expf(x.v[e] - mx);
+    m = mx;
+    s = t;
+  }
+  const float M = block_max(m, sh);
+  s = block_sum(m == -INFINITY ? 0.f : s * __expf(m - M), sh);
+  const float lse = M + logf(s);
+  const int tgt = targets[blockIdx.x];
+  for (int idx = threadIdx.x; idx < ld8; idx += kT) {
+    const F8 x = unpack8(row[idx]);
+    F8 g;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = idx * 8 + e;
+      if (c == tgt) rowloss[blockIdx.x] = lse - x.v[e];
+      g.v[e] = c < V ? (__expf(x.v[e] - lse) - (c == tgt ? 1.f : 0.f)) * inv_T : 0.f;
+    }
+    row[idx] = pack8(g);
+  }
+}
+
 // a = silu(g) * u on [T, 2F] (gate | up) -> [T, F]; i8 runs over T * F/8
 __global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u32x4v *a, int F8n, int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
@@ -813,10 +850,11 @@ twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, co
 }
 
 twist_status twist_ce_fwd_bwd(twist_ctx *ctx, int bf16, void *logits, int64_t ld, const int32_t *targets, float *rowloss, float *loss, int T, int V) {
-  if (bf16 && ld % 8 == 0 && ld <= 16 * 2048 && al16(logits)) {
+  if (bf16 && ld % 8 == 0 && al16(logits)) {
     u32x4v *lv = static_cast<u32x4v *>(logits);
     if (ld <= 4 * 2048) hipLaunchKernelGGL(ce_vec_kernel<4>, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
-    else hipLaunchKernelGGL(ce_vec_kernel<16>, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
+    else if (ld <= 16 * 2048) hipLaunchKernelGGL(ce_vec_kernel<16>, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
+    else hipLaunchKernelGGL(ce_vec_long_kernel, dim3(T), dim3(kT), 0, ctx->stream, lv, ld / 8, targets, rowloss, V, 1.f / (float)T);
   } else
     LAUNCH_BF(ce_kernel, bf16, dim3(T), dim3(kT), logits, ld, targets, rowloss, V, 1.f / (float)T);
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kT), 0, ctx->stream, rowloss, (int64_t)T, 1.f / (float)T, loss);

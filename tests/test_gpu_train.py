@@ -47,6 +47,8 @@ CASES = {
     "gpt_bf16_n384": (replace(si.CFG2, n_layers=1, d_model=192, n_heads=6, d_head=64, d_ff=768, vocab=515, max_seq=384), 2, 3, 384, 2, 384),
     # 1024 tokens: the weight-gradient projections (contraction over the tokens) take the split-contraction path
     "llama_bf16_t1024": (replace(si.CFG3, n_layers=2, d_model=128, n_heads=2, d_head=64, d_ff=256, vocab=300, max_seq=256), 2, 1, 128, 4, 256),
+    # vocabulary above 32768: the cross-entropy kernel that re-reads the row instead of holding it in registers
+    "gpt_bf16_bigvocab": (replace(si.CFG2, n_layers=1, d_model=64, n_heads=2, d_head=32, d_ff=128, vocab=33001, max_seq=32), 2, 1, 64, 2, 32),
     "block_llama_bf16": (replace(si.CFG4, n_layers=1, d_model=256, n_heads=4, d_head=64, d_ff=512, max_seq=128), 2, 2, 256, 2, 128),
 }
 # the same models with the output projections stored unit-major (their three projections change form)
