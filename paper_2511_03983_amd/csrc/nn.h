@@ -48,18 +48,25 @@ twist_status twist_norm_fwd(twist_ctx *ctx, int bf16, int rms, const float *x, c
 // dx (+)= norm backward of dy; dxb = activation-type copy of the resulting dx (may be null);
 // dw, db (fp32, overwritten; db may be null); partial: scratch of at least norm_partial_floats(T, D).
 // With defer_reduce the per-chunk partial sums are left in `partial` and dw/db are not written: the caller later sums
-// many such buffers with one twist_norm_reduce_batch launch (same summation order, hence the same bits).
+// many such buffers with one twist_col_reduce_batch launch (items {partial, dw, 2 D, D, 1} and {partial + D, db, 2 D, D, 1};
+// same summation order, hence the same bits).
 twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, const float *x, const void *w, const float *stats, float *dx,
                             int accumulate, void *dxb, float *dw, float *db, float *partial, int T, int D, bool defer_reduce = false);
 size_t twist_norm_partial_floats(int T, int D);
-struct NormReduce {
+// One deferred column reduction: out[c] = alpha * sum over the T/16-row chunks k of partial[k * stride + c], c < n.
+struct ColReduce {
   const float *partial;
-  float *dw, *db;  // db may be null
+  float *out;
+  int64_t stride;
+  int n;
+  float alpha;
 };
-twist_status twist_norm_reduce_batch(twist_ctx *ctx, const NormReduce *items, int n, int T, int D);
+twist_status twist_col_reduce_batch(twist_ctx *ctx, const ColReduce *items, int n_items, int T);
 
-// column sums: out[n] = alpha * sum_t src[t, n] (fp32, overwritten); partial scratch >= colsum_partial_floats
-twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int Ncols);
+// column sums: out[n] = alpha * sum_t src[t, n] (fp32, overwritten); partial scratch >= colsum_partial_floats.
+// With defer_reduce only the per-chunk sums are written (stride Ncols); the caller reduces them later in a batch.
+twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int Ncols,
+                          bool defer_reduce = false);
 size_t twist_colsum_partial_floats(int T, int Ncols);
 
 // cos/sin table [N, dh/2, 2] (computed in fp64), then in-place rotation of the q and k heads of a fused qkv buffer

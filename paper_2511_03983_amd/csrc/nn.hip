@@ -256,32 +256,27 @@ __global__ __launch_bounds__(kT) void reduce_partial_kernel(const float *partial
   }
 }
 
-// the same reduction for a batch of norm layers in one launch: blockIdx.y = layer, and both parameter gradients
+// the same reduction for a batch of buffers in one launch: blockIdx.y = item
 constexpr int kReduceBatch = 64;
-struct NormReduceArgs {
-  NormReduce item[kReduceBatch];
+struct ColReduceArgs {
+  ColReduce item[kReduceBatch];
 };
-__global__ __launch_bounds__(kT) void reduce_partial_batch_kernel(const NormReduceArgs a, int n_chunks, int D) {
+__global__ __launch_bounds__(kT) void reduce_partial_batch_kernel(const ColReduceArgs a, int n_chunks) {
   __shared__ float sh[16][16];
-  const NormReduce it = a.item[blockIdx.y];
+  const ColReduce it = a.item[blockIdx.y];
   const int col = threadIdx.x & 15, slice = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + col;
-  for (int which = 0; which < 2; ++which) {
-    float *out = which ? it.db : it.dw;
-    if (!out) continue;  // uniform over the workgroup
-    const float *partial = it.partial + which * D;
-    float s = 0.f;
-    if (c < D)
-      for (int k = slice; k < n_chunks; k += 16) s += partial[(int64_t)k * 2 * D + c];
-    __syncthreads();
-    sh[slice][col] = s;
-    __syncthreads();
-    if (slice == 0 && c < D) {
-      float t = 0.f;
+  if (blockIdx.x * 16 >= it.n) return;  // uniform over the workgroup
+  float s = 0.f;
+  if (c < it.n)
+    for (int k = slice; k < n_chunks; k += 16) s += it.partial[(int64_t)k * it.stride + c];
+  sh[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && c < it.n) {
+    float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) t += sh[i][col];
-      out[c] = 1.f * t;
-    }
+    for (int i = 0; i < 16; ++i) t += sh[i][col];
+    it.out[c] = it.alpha * t;
   }
 }
 
@@ -786,21 +781,24 @@ twist_status twist_norm_bwd(twist_ctx *ctx, int bf16, int rms, const void *dy, c
   return TWIST_OK;
 }
 
-twist_status twist_norm_reduce_batch(twist_ctx *ctx, const NormReduce *items, int n, int T, int D) {
+twist_status twist_col_reduce_batch(twist_ctx *ctx, const ColReduce *items, int n_items, int T) {
   const int nc = n_chunks(T);
-  for (int i0 = 0; i0 < n; i0 += kReduceBatch) {
-    NormReduceArgs a;
-    const int m = std::min(kReduceBatch, n - i0);
-    for (int i = 0; i < m; ++i) a.item[i] = items[i0 + i];
-    hipLaunchKernelGGL(reduce_partial_batch_kernel, dim3((D + 15) / 16, m), dim3(kT), 0, ctx->stream, a, nc, D);
+  for (int i0 = 0; i0 < n_items; i0 += kReduceBatch) {
+    ColReduceArgs a;
+    const int m = std::min(kReduceBatch, n_items - i0);
+    int widest = 1;
+    for (int i = 0; i < m; ++i) { a.item[i] = items[i0 + i]; widest = std::max(widest, items[i0 + i].n); }
+    hipLaunchKernelGGL(reduce_partial_batch_kernel, dim3((widest + 15) / 16, m), dim3(kT), 0, ctx->stream, a, nc);
     TW_HIP(ctx, hipGetLastError());
   }
   return TWIST_OK;
 }
 
-twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int n) {
+twist_status twist_colsum(twist_ctx *ctx, int bf16, const void *src, int64_t ld, float alpha, float *out, float *partial, int T, int n,
+                          bool defer_reduce) {
   const int nc = n_chunks(T);
   LAUNCH_BF(colsum_kernel, bf16, dim3((n + 63) / 64, nc), dim3(64), src, ld, partial, T, n);
+  if (defer_reduce) return TWIST_OK;
   hipLaunchKernelGGL(reduce_partial_kernel, dim3((n + 15) / 16), dim3(kT), 0, ctx->stream, partial, (int64_t)n, nc, alpha, out, n);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;

@@ -32,10 +32,12 @@ struct Workspace {
   std::vector<float *> xs;    // residual stream before / inside / after every layer, fp32 [T,D]
   std::vector<float *> stats; // (mean, rstd) per row for each norm
   std::vector<LayerBufs> layer;
-  float *dx, *rope_tab, *rowloss, *partial, *delta;
+  float *dx, *rope_tab, *rowloss, *delta;
   float *splitk;        // scratch of the weight-gradient projections that are cut along the token dimension
   float *norm_partial;  // one block of per-chunk norm-gradient sums per norm layer (2 n_layers + 1), reduced in one launch at the end
   size_t norm_partial_stride;
+  float *bias_partial;  // models with biases: per layer, the per-chunk column sums behind the four bias gradients
+  size_t bias_partial_stride;
   void *dxb, *dxb2, *hf, *logits, *da, *dgu, *dh, *dout, *dqkv;
   int64_t ld_logits;
   size_t bytes;
@@ -75,11 +77,11 @@ void carve(const twist_ctx *ctx, const twist_subnet *sub, int B, int N, void *ba
   w.logits = d.vocab ? c.take(T * w.ld_logits * es) : nullptr;
   w.rowloss = c.take<float>(std::max<size_t>(T, 1024) * 4);
   w.rope_tab = c.take<float>((size_t)N * d.d_head * 4);
-  const size_t widest = std::max({D, 3 * hd_max, (size_t)nf * f_max});
-  w.partial = c.take<float>(std::max(twist_norm_partial_floats((int)T, (int)D), twist_colsum_partial_floats((int)T, (int)widest)) * 4);
   w.splitk = c.take<float>(kSplitkFloats * 4);
   w.norm_partial_stride = align_up(twist_norm_partial_floats((int)T, (int)D), 64);
   w.norm_partial = c.take<float>(w.norm_partial_stride * (2 * (size_t)d.n_layers + 1) * 4);
+  w.bias_partial_stride = d.has_bias ? align_up(twist_colsum_partial_floats((int)T, (int)(2 * D + nf * f_max + 3 * hd_max)), 64) : 0;
+  w.bias_partial = c.take<float>(w.bias_partial_stride * (size_t)d.n_layers * 4);
   w.delta = c.take<float>((size_t)B * h_max * N * 4);
   w.da = c.take(T * f_max * es);
   w.dgu = c.take(T * nf * f_max * es);
@@ -195,10 +197,11 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   // Norm backward of norm layer `idx` (2l, 2l+1: the two norms of layer l; 2 n_layers: the final norm).  Its parameter
   // gradients are left as per-chunk partial sums in the layer's own block and summed for all layers by one launch at
   // the end of the pass, which takes 2 n_layers small kernels off the chain of dependent kernels.
-  std::vector<NormReduce> norm_items;
+  std::vector<ColReduce> reduce_items;
   auto norm_bwd = [&](int idx, const void *dy, const float *x, const void *nw, int accumulate, void *dxb, float *dw, float *db) {
     float *part = w.norm_partial + (size_t)idx * w.norm_partial_stride;
-    norm_items.push_back({part, dw, db});
+    reduce_items.push_back({part, dw, 2 * (int64_t)D, D, 1.f});
+    if (db) reduce_items.push_back({part + D, db, 2 * (int64_t)D, D, 1.f});
     return twist_norm_bwd(ctx, bf, rms, dy, x, nw, w.stats[idx], w.dx, accumulate, dxb, dw, db, part, T, D, true);
   };
 
@@ -269,7 +272,15 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     const LayerBufs &b = w.layer[l];
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     // FFN branch: y = c_f (a W_down^T + b_down)
-    if (L.at(l, TWIST_B_DOWN).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx, D, c_f, G(L.at(l, TWIST_B_DOWN)), w.partial, T, D));
+    // bias gradients: per-chunk column sums now (into this layer's block), reduced with everything else at the end
+    float *bias_part = w.bias_partial + (size_t)l * w.bias_partial_stride;
+    auto bias_grad = [&](const void *src, int64_t ld, float alpha, float *out, int n) {
+      float *part = bias_part;
+      bias_part += twist_colsum_partial_floats(T, n);
+      reduce_items.push_back({part, out, (int64_t)n, n, alpha});
+      return twist_colsum(ctx, bf, src, ld, alpha, out, part, T, n, true);
+    };
+    if (L.at(l, TWIST_B_DOWN).off >= 0) TW_TRY(bias_grad(gx, D, c_f, G(L.at(l, TWIST_B_DOWN)), D));
     TW_TRY(side.fork(0));
     if (um) TW_TRY(wgrad(F, D, b.a, F, gx, D, G(L.at(l, TWIST_W_DOWN)), c_f));
     else TW_TRY(wgrad(D, F, gx, D, b.a, F, G(L.at(l, TWIST_W_DOWN)), c_f));
@@ -279,7 +290,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(mask(w.da, l, TWIST_KIND_FFN, d.ffn_granule));
     TW_TRY(side.wait_done(1));
     TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F));
-    if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), w.partial, T, nf * F));
+    if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(bias_grad(w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), nf * F));
     TW_TRY(side.fork(1));
     TW_TRY(wgrad(nf * F, D, w.dgu, nf * F, b.h2, D, G(w1), 1.f));
     TW_TRY(side.done(1));
@@ -287,7 +298,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.wait_done(2));
     TW_TRY(norm_bwd(2 * l + 1, w.dh, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), 1, gx_other, G(L.at(l, TWIST_NORM2_W)), G(L.at(l, TWIST_NORM2_B))));
     // attention branch: y = c_a (o C_attn^T + b_o)
-    if (L.at(l, TWIST_BO).off >= 0) TW_TRY(twist_colsum(ctx, bf, gx_other, D, c_a, G(L.at(l, TWIST_BO)), w.partial, T, D));
+    if (L.at(l, TWIST_BO).off >= 0) TW_TRY(bias_grad(gx_other, D, c_a, G(L.at(l, TWIST_BO)), D));
     TW_TRY(side.fork(2));
     if (um) TW_TRY(wgrad(HD, D, b.o, HD, gx_other, D, G(L.at(l, TWIST_WO)), c_a));
     else TW_TRY(wgrad(D, HD, gx_other, D, b.o, HD, G(L.at(l, TWIST_WO)), c_a));
@@ -297,7 +308,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(mask(w.dout, l, TWIST_KIND_HEAD, dh));
     TW_TRY(side.wait_done(3));
     TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh, d.use_rope ? w.rope_tab : nullptr));
-    if (L.at(l, TWIST_BQ).off >= 0) TW_TRY(twist_colsum(ctx, bf, w.dqkv, 3 * HD, 1.f, G(L.at(l, TWIST_BQ)), w.partial, T, 3 * HD));
+    if (L.at(l, TWIST_BQ).off >= 0) TW_TRY(bias_grad(w.dqkv, 3 * HD, 1.f, G(L.at(l, TWIST_BQ)), 3 * HD));
     TW_TRY(side.fork(3));
     TW_TRY(wgrad(3 * HD, D, w.dqkv, 3 * HD, b.h1, D, G(L.at(l, TWIST_WQ)), 1.f));
     TW_TRY(side.done(3));
@@ -305,7 +316,7 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.wait_done(0));
     TW_TRY(norm_bwd(2 * l, w.dh, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), 1, gx, G(L.at(l, TWIST_NORM1_W)), G(L.at(l, TWIST_NORM1_B))));
   }
-  TW_TRY(twist_norm_reduce_batch(ctx, norm_items.data(), (int)norm_items.size(), T, D));
+  TW_TRY(twist_col_reduce_batch(ctx, reduce_items.data(), (int)reduce_items.size(), T));
   for (int i = 0; i < 4; ++i) TW_TRY(side.wait_done(i));  // join: the caller's stream sees the whole pass
   (void)gx_other;
 
