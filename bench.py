@@ -404,6 +404,32 @@ def cpu_baseline(si):
                       f"({times[1]:.2f} s, {times[2]:.2f} s) and extrapolated to 22 layers"}
 
 
+def cpu_baseline_movers(si):
+    """The CPU checker's extract and aggregate on a bounded sample of the mover workload: ONE Llama-7B-shaped layer at a
+    quarter of its width (d_model 4096, 8 of 32 heads, d_ff 2752 of 11008: same row lengths, a quarter of the rows),
+    S=8 half-width subnets.  GB/s is quoted on the workload's own algorithmic bytes (2-byte elements), like the GPU's."""
+    import numpy as np
+    from oracle import move as omove
+    from oracle.sample import sample_plan
+    cfg = replace(si.CFG4, n_layers=1, n_heads=8, d_ff=2752)
+    S, hs, fs = 8, 4, 1376
+    full = si.make_weights(cfg, 0)
+    plan = sample_plan(1, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 0)
+    t0 = time.perf_counter()
+    subs = [omove.extract(full, plan, s, cfg.d_head) for s in range(S)]
+    t_ex = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    omove.aggregate(full, plan, subs, cfg.d_head)
+    t_ag = time.perf_counter() - t0
+    n_full = sum(v.size for v in full["layers"][0].values())
+    n_sub = sum(v.size for v in subs[0]["layers"][0].values())
+    ex_bytes, ag_bytes = 2 * 2 * n_sub * S, 2 * (S * n_sub + n_full)
+    return {"value": (ex_bytes + ag_bytes) / (t_ex + t_ag) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "extract_GBps": ex_bytes / t_ex / 1e9, "aggregate_GBps": ag_bytes / t_ag / 1e9,
+            "sample": f"fp64 numpy checker, extract x{S} ({t_ex:.1f} s) and aggregate ({t_ag:.1f} s) of one Llama-7B-shaped layer at quarter "
+                      "width (8 heads, d_ff 2752), bytes counted as 2-byte elements"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -473,6 +499,9 @@ def main():
             "traffic_unit": "bytes per layer (8 extract launches + 1 aggregate launch) behind the L2",
             "algorithmic_bytes_per_layer": (movers["extract_alg_GB"] + movers["aggregate_alg_GB"]) * 1e9 / 32}
         out["movers_llama7b_stack_out_in_layout"] = movers_rm
+    if not args.skip_cpu and not args.skip_movers:
+        out["cpu_baseline_movers"] = cpu_baseline_movers(si)
+        log("[bench] cpu baseline (movers):", json.dumps(out["cpu_baseline_movers"]))
     if clock:
         out["clock_under_projection_load"] = clock
     if golden:

@@ -2,10 +2,13 @@
 
     python -m paper_2511_03983_amd.profile_summary stats <x_kernel_stats.csv> <out.txt> "<command that was profiled>"
     python -m paper_2511_03983_amd.profile_summary pmc   <x_counter_collection.csv> <out.txt> "<command that was profiled>"
+    python -m paper_2511_03983_amd.profile_summary mfma  <x_counter_collection.csv> <out.txt> "<command that was profiled>"
 
 `stats` takes the per-kernel table of `rocprofv3 --kernel-trace --stats --output-format csv`; `pmc` takes the
 per-dispatch counter table of `rocprofv3 --pmc <counter> --output-format csv`, sums the rows of each dispatch and
-averages per (kernel, grid size).  Kernel names are shortened; rows of other libraries' kernels are kept but
+averages per (kernel, grid size); `mfma` takes a run with SQ_VALU_MFMA_BUSY_CYCLES, SQ_BUSY_CYCLES and
+SQ_INSTS_VALU_MFMA_MOPS_BF16 and prints one row per kernel with the matrix-pipe utilisation derived from them.
+Kernel names are shortened; rows of other libraries' kernels are kept but
 marked.  FETCH_SIZE / WRITE_SIZE are reported by the tool in KiB per dispatch.
 """
 from __future__ import annotations
@@ -58,7 +61,35 @@ def pmc(src: str, out: str, cmd: str) -> None:
             f.write(f"{kn:78s} {grid:>10s} {cname:>12s} {n:10d} {tot / n:18.1f}\n")
 
 
+def mfma(src: str, out: str, cmd: str) -> None:
+    """MFMA_BUSY counts, summed over the chip's 1024 SIMDs, the cycles a SIMD's matrix pipe is occupied (32 per
+    32x32x16 bf16 instruction); SQ_BUSY_CYCLES counts the kernel's cycles once per shader engine (32 of them).
+    Utilisation = MFMA_BUSY / (32 x SQ_BUSY_CYCLES): the fraction of all SIMD-cycles with the matrix pipe busy."""
+    disp = collections.OrderedDict()
+    with open(src, newline="") as f:
+        for r in csv.DictReader(f):
+            key = r["Dispatch_Id"]
+            d = disp.setdefault(key, {"k": short(r["Kernel_Name"])})
+            d[r["Counter_Name"]] = d.get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+    agg = collections.defaultdict(lambda: collections.defaultdict(float))
+    for d in disp.values():
+        a = agg[d["k"]]
+        a["n"] += 1
+        for c in ("SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "SQ_INSTS_VALU_MFMA_MOPS_BF16"):
+            a[c] += d.get(c, 0.0)
+    with open(out, "w") as f:
+        f.write("# matrix-pipe utilisation per kernel from one rocprofv3 --pmc run (sums over all dispatches of the kernel)\n# command: %s\n" % cmd)
+        f.write("# utilisation = SQ_VALU_MFMA_BUSY_CYCLES / (32 x SQ_BUSY_CYCLES): MFMA_BUSY is summed over the 1024 SIMDs, BUSY_CYCLES over 32 shader engines\n")
+        f.write(f"{'kernel':60s} {'dispatches':>10s} {'mfma_busy_cycles':>18s} {'busy_cycles':>14s} {'mfma_mops_bf16':>16s} {'utilisation':>12s}\n")
+        for k, a in sorted(agg.items(), key=lambda x: -x[1]["SQ_VALU_MFMA_BUSY_CYCLES"]):
+            if k.startswith("other:") or a["SQ_BUSY_CYCLES"] <= 0:
+                continue
+            f.write(f"{k[:60]:60s} {int(a['n']):10d} {a['SQ_VALU_MFMA_BUSY_CYCLES']:18.0f} {a['SQ_BUSY_CYCLES']:14.0f} "
+                    f"{a['SQ_INSTS_VALU_MFMA_MOPS_BF16']:16.0f} {a['SQ_VALU_MFMA_BUSY_CYCLES'] / (32.0 * a['SQ_BUSY_CYCLES']):12.3f}\n")
+
+
 if __name__ == "__main__":
-    if len(sys.argv) != 5 or sys.argv[1] not in ("stats", "pmc"):
+    modes = {"stats": stats, "pmc": pmc, "mfma": mfma}
+    if len(sys.argv) != 5 or sys.argv[1] not in modes:
         sys.exit(__doc__)
-    (stats if sys.argv[1] == "stats" else pmc)(sys.argv[2], sys.argv[3], sys.argv[4])
+    modes[sys.argv[1]](sys.argv[2], sys.argv[3], sys.argv[4])
