@@ -270,6 +270,40 @@ def test_scale_mode_none_and_shape_errors(lib):
         ctx.twist_workspace_bytes(sub, 1, cfg.max_seq + 1)
 
 
+def test_round_and_running_aggregate_reject_bad_arguments(lib):
+    """Error paths of twist_round and twist_aggregate_begin/add: every one is refused on the host, nothing is launched."""
+    cfg, S, hs, fs, B, N = CASES["gpt_f32"]
+    full_t = to_device(si.make_weights(cfg, 1, std=0.05, generic=True), cfg)
+    before = {k: v.clone() for k, v in full_t["layers"][0].items()}
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    sb, wb, ib = ctx.twist_round_bytes(S, hs, fs, B, N, 1)
+    slab, ws, image = (torch.empty(n, dtype=torch.uint8, device="cuda") for n in (sb, wb, ib))
+    x = torch.zeros(S, 1, B, N, dtype=torch.int32, device="cuda")
+    losses = torch.zeros(S, 1, device="cuda")
+    with pytest.raises(lib.TwistError):                      # subnet slab too small
+        ctx.twist_round(fw, x, x, S, hs, fs, slab[:sb // 2], ws, image, losses)
+    with pytest.raises(lib.TwistError):                      # running-sum image too small
+        ctx.twist_round(fw, x, x, S, hs, fs, slab, ws, image[:ib // 2], losses)
+    with pytest.raises(lib.TwistError):                      # workspace too small
+        ctx.twist_round(fw, x, x, S, hs, fs, slab, ws[:1024], image, losses)
+    with pytest.raises(lib.TwistError):                      # the size bound below Algorithm 1: 3 subnets of 1 head cannot cover 6
+        ctx.twist_round(fw, x, x, S, 1, fs, slab, ws, image, losses)
+    with pytest.raises(lib.TwistError):                      # no local step at all
+        ctx.twist_round(fw, x[:, :0], x[:, :0], S, hs, fs, slab, ws, image, losses)
+    torch.cuda.synchronize()
+    for k, v in before.items():                              # the central model was not touched by any refused call
+        assert torch.equal(v, full_t["layers"][0][k]), k
+    plan = ctx.twist_sample(S, hs, fs, seed=1)
+    other = ctx.twist_sample(S, hs, fs, seed=2)
+    with pytest.raises(lib.TwistError):                      # misaligned image
+        ctx.twist_aggregate_begin(plan, image[8:])
+    acc = ctx.twist_aggregate_begin(plan, image)
+    with pytest.raises(lib.TwistError):                      # a subnet of another plan
+        acc.twist_aggregate_add(ctx.twist_extract(other, fw, 0))
+    acc.close()
+
+
 def test_work_is_enqueued_on_the_contexts_stream(lib):
     """A context created on a non-default stream gives the same bits as one on the default stream (every kernel,
     the second stream's included, is ordered on the stream the caller handed over)."""
