@@ -364,13 +364,19 @@ def bench_latency_ablation(args, tw, si, torch):
         for _ in range(reps):
             ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
             ctx.twist_subnet_step(sub, tw.OPT_ADAMW, lr=1e-4)
-        b = ev(); b.record(); torch.cuda.synchronize()
+        b = ev(); b.record()
+        for _ in range(reps):                       # deployment use of the same subnet: forward only (Section 4.2)
+            ctx.twist_subnet_forward(sub, x, y, ws, loss)
+        c = ev(); c.record(); torch.cuda.synchronize()
         sub.close(); plan.close()
-        return a.elapsed_time(b) / reps
+        return a.elapsed_time(b) / reps, b.elapsed_time(c) / reps
 
-    res = {"batch": [B, N], "full_width_ms": ms_per_batch(12, 12)}
+    full = ms_per_batch(12, 12)
+    res = {"batch": [B, N], "full_width_ms": full[0], "full_width_forward_ms": full[1]}
     for k in (10, 8, 6, 4):
-        res[f"kappa_{k}"] = {"attn_ms": ms_per_batch(k, 12), "ffn_ms": ms_per_batch(12, k), "both_ms": ms_per_batch(k, k)}
+        at, ff, bo = ms_per_batch(k, 12), ms_per_batch(12, k), ms_per_batch(k, k)
+        res[f"kappa_{k}"] = {"attn_ms": at[0], "ffn_ms": ff[0], "both_ms": bo[0],
+                             "attn_forward_ms": at[1], "ffn_forward_ms": ff[1], "both_forward_ms": bo[1]}
     return res
 
 
