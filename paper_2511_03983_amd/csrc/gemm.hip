@@ -485,10 +485,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
         }
         if (ep.out_f32) {
           const f32x4 w = {v[0], v[1], v[2], v[3]};
-          *reinterpret_cast<f32x4 *>(static_cast<float *>(outp) + o) = w;
+          __builtin_nontemporal_store(w, reinterpret_cast<f32x4 *>(static_cast<float *>(outp) + o));
         } else {
           const u32x2 w = {(uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16)};
-          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outp) + o) = w;
+          __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outp) + o));
         }
       } else {
 #pragma unroll
