@@ -127,6 +127,38 @@ def test_fwd_bwd_matches_oracle(lib, name):
             _compare_grads(cfg, got, ograds, tol, name)
 
 
+def test_fwd_bwd_at_the_benchmark_widths_matches_oracle(lib):
+    """One layer at the Llama-1B workload's real widths (d_model 2048, 8 of 16 heads of 128, 2816 of 5632 neurons,
+    vocabulary 32000) on 256 tokens: every contraction length, the head size and the vocabulary of the bench, end to end
+    against the checker (the bench's 8192 tokens are out of its reach; test_gpu_fullsize.py covers that shape kernel by
+    kernel)."""
+    cfg = replace(si.CFG3, n_layers=1, max_seq=256, out_unit_major=True)
+    S, hs, fs, B, N = 2, 8, 2816, 1, 256
+    full_np = si.make_weights(cfg, 7, std=0.02, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=8)
+    oplan = sample_plan(cfg.n_layers, cfg.n_heads, cfg.n_ffn_units, S, hs, fs, 8)
+    fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+    t = si.tokens_zipf(cfg.vocab, B, N, 4)
+    x_np, y_np = t[:, :-1].copy(), t[:, 1:].copy()
+    x, y = torch.tensor(x_np).cuda(), torch.tensor(y_np).cuda()
+    loss = torch.zeros(1, device="cuda")
+    sub = ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS)
+    ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+    ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+    torch.cuda.synchronize()
+    got = subnet_to_numpy(sub, cfg, GRAD)
+    osub = omove.extract(full_np, oplan, 0, cfg.d_head, cfg.ffn_granule)
+    oloss, ograds = omodel.forward_backward(cfg, osub, x_np, y_np)
+    rloss, rgrads = omodel.forward_backward(cfg, osub, x_np, y_np, q=_round_hook)
+    assert abs(loss.item() - oloss) <= 5e-3 * abs(oloss), (loss.item(), oloss)
+    assert abs(loss.item() - rloss) <= 5e-3 * abs(rloss), (loss.item(), rloss)
+    worst = _compare_grads(cfg, got, ograds, 5e-3, "llama1b widths/exact", fmt=(rgrads, ograds))
+    _compare_grads(cfg, got, rgrads, 5e-3, "llama1b widths/rounded", fmt=(rgrads, ograds))
+    print(f"llama1b widths: worst rel. error vs exact fp64 checker {worst:.2e}")
+
+
 @pytest.mark.parametrize("name,opt", [("cfg1_block_f32", "sgd"), ("llama_f32", "adamw"), ("llama_bf16", "adamw"), ("gpt_bf16", "sgd"),
                                       ("llama_bf16_um", "adamw")])
 def test_local_steps_then_aggregate(lib, name, opt):
