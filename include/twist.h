@@ -164,6 +164,13 @@ TWIST_API twist_status twist_subnet_bytes(twist_ctx *ctx, const twist_plan *plan
  * matrix and gate/up as one [2 F', d] matrix; twist_subnet_view hides that. */
 TWIST_API twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int32_t s,
                            void *storage, size_t storage_bytes, int32_t store, twist_subnet **out);
+/* The dispatcher for all S subnets of the plan at once (Section 3.2; on one device all subnets are resident together):
+ * same result as twist_extract for s = 0..S-1 into storages[s] (each dev, 256-byte aligned, storage_bytes large), but
+ * every tensor that is cut into blocks of whole rows, and every shared matrix, is read ONCE and written to each subnet
+ * that holds the block, instead of once per subnet (up to 8 subnets; beyond that the per-subnet gathers run).
+ * out[0..S) receives the handles; on error none is created. */
+TWIST_API twist_status twist_extract_all(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, void *const *storages,
+                                         size_t storage_bytes, int32_t store, twist_subnet **out);
 /* Device pointer and [rows, cols] shape (cols = 1 for vectors) of one subnet tensor; layer = -1 selects the
  * model-level tensors.  what = TWIST_PARAM gives desc.dtype data, TWIST_GRAD the fp32 gradient. */
 TWIST_API twist_status twist_subnet_view(const twist_subnet *sub, int32_t layer, int32_t tensor, int32_t what,

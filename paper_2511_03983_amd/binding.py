@@ -78,6 +78,7 @@ _SIGS = {
     "twist_plan_destroy": ([_vp], None),
     "twist_subnet_bytes": ([_vp, _vp, _i32, C.POINTER(_sz)], _i32),
     "twist_extract": ([_vp, _vp, C.POINTER(FullWeightsC), _i32, _vp, _sz, _i32, C.POINTER(_vp)], _i32),
+    "twist_extract_all": ([_vp, _vp, C.POINTER(FullWeightsC), C.POINTER(_vp), _sz, _i32, C.POINTER(_vp)], _i32),
     "twist_subnet_view": ([_vp, _i32, _i32, _i32, C.POINTER(_vp), C.POINTER(C.c_int64)], _i32),
     "twist_subnet_destroy": ([_vp], None),
     "twist_workspace_bytes": ([_vp, _vp, _i32, _i32, C.POINTER(_sz)], _i32),
@@ -158,6 +159,16 @@ class Context:
         h = _vp()
         _check(lib.twist_extract(self.h, plan.h, C.byref(full.c), s, _vp(storage.data_ptr()), storage.numel(), store, C.byref(h)), self.h)
         return Subnet(self, plan, h, storage, s)
+
+    def twist_extract_all(self, plan: "Plan", full: "FullWeights", store=STORE_PARAMS, storages=None):
+        """All S subnets of the plan in one pass over the central model; returns the list of Subnet holders."""
+        if storages is None:
+            nb = self.twist_subnet_bytes(plan, store)
+            storages = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(plan.S)]
+        ptrs = (_vp * plan.S)(*[st.data_ptr() for st in storages])
+        hs = (_vp * plan.S)()
+        _check(lib.twist_extract_all(self.h, plan.h, C.byref(full.c), ptrs, min(st.numel() for st in storages), store, hs), self.h)
+        return [Subnet(self, plan, _vp(hs[s]), storages[s], s) for s in range(plan.S)]
 
     def twist_workspace_bytes(self, sub: "Subnet", B: int, N: int) -> int:
         n = _sz()

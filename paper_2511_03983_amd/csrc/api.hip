@@ -401,8 +401,10 @@ twist_status check_full(twist_ctx *ctx, const twist_full_weights *full, const ch
 
 // Run `launch` over every layer (and once for the model-level tensors).  A layer's row-block jobs go into one
 // launch and its other jobs into a second one when aggregating (which has a lighter kernel for the former).
+enum JobFilter { JOBS_ALL = 0, JOBS_ROW_BLOCKS = 1, JOBS_NOT_ROW_BLOCKS = 2 };
 template <class F>
-twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int s, bool for_aggregate, MoveLaunch &ml, F launch) {
+twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int s, bool for_aggregate, MoveLaunch &ml, F launch,
+                            JobFilter filter = JOBS_ALL) {
   const twist_model_desc &d = ctx->d;
   for (int l = -1; l < d.n_layers; ++l) {
     const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
@@ -414,6 +416,7 @@ twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_
         MoveJob &jb = ml.job[ml.n_jobs];
         if (!make_job(ctx, plan, l, t, fp, s, for_aggregate, ml.n_subs, jb)) continue;
         if (for_aggregate && (jb.vec == 2) != (pass == 0)) continue;
+        if ((filter == JOBS_ROW_BLOCKS && jb.vec != 2) || (filter == JOBS_NOT_ROW_BLOCKS && jb.vec == 2)) continue;
         jb.blk_begin = blocks;
         blocks += job_blocks(jb);
         ++ml.n_jobs;
@@ -426,19 +429,18 @@ twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_
 
 }  // namespace
 
-extern "C" twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int32_t s, void *storage,
-                                      size_t storage_bytes, int32_t store, twist_subnet **out) {
-  if (!ctx || !plan || !storage || !out) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: null argument");
-  if (plan->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: plan belongs to another context");
-  if (s < 0 || s >= plan->S) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: subnet %d outside [0, %d)", s, plan->S);
-  TW_TRY(check_full(ctx, full, "twist_extract"));
+namespace {
+
+// checks and the subnet object over caller storage (no device work)
+twist_status bind_subnet(twist_ctx *ctx, const twist_plan *plan, int32_t s, void *storage, size_t storage_bytes, int32_t store, const char *who,
+                         twist_subnet **out) {
+  if (s < 0 || s >= plan->S) TW_FAIL(ctx, TWIST_EINVAL, "%s: subnet %d outside [0, %d)", who, s, plan->S);
   size_t need;
   TW_TRY(twist_subnet_bytes(ctx, plan, store, &need));
-  if (storage_bytes < need) TW_FAIL(ctx, TWIST_ESHAPE, "twist_extract: storage of %zu bytes is smaller than the %zu needed", storage_bytes, need);
-  if (reinterpret_cast<uintptr_t>(storage) % 256) TW_FAIL(ctx, TWIST_ESHAPE, "twist_extract: storage must be 256-byte aligned");
-
+  if (storage_bytes < need) TW_FAIL(ctx, TWIST_ESHAPE, "%s: storage of %zu bytes is smaller than the %zu needed", who, storage_bytes, need);
+  if (reinterpret_cast<uintptr_t>(storage) % 256) TW_FAIL(ctx, TWIST_ESHAPE, "%s: storage must be 256-byte aligned", who);
   twist_subnet *sub = new (std::nothrow) twist_subnet;
-  if (!sub) TW_FAIL(ctx, TWIST_ENOMEM, "twist_extract: out of host memory");
+  if (!sub) TW_FAIL(ctx, TWIST_ENOMEM, "%s: out of host memory", who);
   sub->ctx = ctx; sub->plan = plan; sub->s = s; sub->store = store;
   sub->base = static_cast<char *>(storage);
   const size_t pb = region_bytes(plan, ctx->esize()), fb = region_bytes(plan, 4);
@@ -452,20 +454,77 @@ extern "C" twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, co
     sub->adam_m = reinterpret_cast<float *>(p); p += fb;
     sub->adam_v = reinterpret_cast<float *>(p); p += fb;
   }
+  *out = sub;
+  return TWIST_OK;
+}
+
+// after the weights are in place: fp32 master copy, zeroed gradient and moment regions
+twist_status finish_subnet(twist_ctx *ctx, const twist_plan *plan, twist_subnet *sub) {
+  const size_t fb = region_bytes(plan, 4);
+  if (sub->master) TW_TRY(twist_launch_to_f32(ctx, sub->params, sub->master, plan->layout.n_total));
+  if (sub->grads) TW_TRY(twist_launch_zero(ctx, sub->grads, fb));
+  if (sub->adam_m) TW_TRY(twist_launch_zero(ctx, sub->adam_m, 2 * fb));
+  return TWIST_OK;
+}
+
+}  // namespace
+
+extern "C" twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int32_t s, void *storage,
+                                      size_t storage_bytes, int32_t store, twist_subnet **out) {
+  if (!ctx || !plan || !storage || !out) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: null argument");
+  if (plan->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: plan belongs to another context");
+  if (s < 0 || s >= plan->S) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract: subnet %d outside [0, %d)", s, plan->S);
+  TW_TRY(check_full(ctx, full, "twist_extract"));
+  twist_subnet *sub = nullptr;
+  TW_TRY(bind_subnet(ctx, plan, s, storage, storage_bytes, store, "twist_extract", &sub));
   // The few elements of padding between tensors are never read by any kernel except the optimizer
   // sweeps, whose results there are never used, so the weight slab is not cleared (clearing it would
   // add a full extra write of the subnet).
-  twist_status st = TWIST_OK;
   MoveLaunch ml;
   std::memset(&ml, 0, sizeof ml);
   ml.sub_base[0] = sub->params;
-  if (st == TWIST_OK)
-    st = for_each_group(ctx, plan, full, s, false, ml, [&](const MoveLaunch &m, int blocks) { return twist_launch_extract(ctx, m, blocks); });
-  if (st == TWIST_OK && sub->master) st = twist_launch_to_f32(ctx, sub->params, sub->master, plan->layout.n_total);
-  if (st == TWIST_OK && sub->grads) st = twist_launch_zero(ctx, sub->grads, fb);
-  if (st == TWIST_OK && sub->adam_m) st = twist_launch_zero(ctx, sub->adam_m, 2 * fb);
+  twist_status st = for_each_group(ctx, plan, full, s, false, ml, [&](const MoveLaunch &m, int blocks) { return twist_launch_extract(ctx, m, blocks); });
+  if (st == TWIST_OK) st = finish_subnet(ctx, plan, sub);
   if (st != TWIST_OK) { delete sub; return st; }
   *out = sub;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_extract_all(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, void *const *storages,
+                                          size_t storage_bytes, int32_t store, twist_subnet **out) {
+  if (!ctx || !plan || !storages || !out) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract_all: null argument");
+  if (plan->ctx != ctx) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract_all: plan belongs to another context");
+  TW_TRY(check_full(ctx, full, "twist_extract_all"));
+  const int S = plan->S;
+  for (int s = 0; s < S; ++s)
+    if (!storages[s]) TW_FAIL(ctx, TWIST_EINVAL, "twist_extract_all: storage %d is NULL", s);
+  std::vector<twist_subnet *> subs(S, nullptr);
+  twist_status st = TWIST_OK;
+  for (int s = 0; s < S && st == TWIST_OK; ++s) st = bind_subnet(ctx, plan, s, storages[s], storage_bytes, store, "twist_extract_all", &subs[s]);
+  const bool fused = S <= 8;  // the one-pass kernel keeps up to 8 destinations per group of central vectors
+  if (st == TWIST_OK && fused) {
+    // tensors cut into blocks of whole rows (and the shared matrices): one pass over the central tensor writes every subnet
+    MoveLaunch ml;
+    std::memset(&ml, 0, sizeof ml);
+    ml.n_subs = S;
+    for (int s = 0; s < S; ++s) { ml.sub_base[s] = subs[s]->params; ml.sub_row[s] = s; }
+    st = for_each_group(ctx, plan, full, 0, true, ml, [&](const MoveLaunch &m, int blocks) { return twist_launch_extract_all(ctx, m, blocks); },
+                        JOBS_ROW_BLOCKS);
+  }
+  for (int s = 0; s < S && st == TWIST_OK; ++s) {  // everything else (or everything, beyond 8 subnets): per-subnet gathers
+    MoveLaunch ml;
+    std::memset(&ml, 0, sizeof ml);
+    ml.n_subs = S;  // same job classification as above
+    ml.sub_base[0] = subs[s]->params;
+    st = for_each_group(ctx, plan, full, s, false, ml, [&](const MoveLaunch &m, int blocks) { return twist_launch_extract(ctx, m, blocks); },
+                        fused ? JOBS_NOT_ROW_BLOCKS : JOBS_ALL);
+    if (st == TWIST_OK) st = finish_subnet(ctx, plan, subs[s]);
+  }
+  if (st != TWIST_OK) {
+    for (twist_subnet *p : subs) delete p;
+    return st;
+  }
+  for (int s = 0; s < S; ++s) out[s] = subs[s];
   return TWIST_OK;
 }
 

@@ -15,6 +15,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kChunk = 8;  // subnets handled together (loads issued together in the pull, destinations in the push)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -159,6 +160,45 @@ __device__ __forceinline__ void gather_rows(const MoveJob &jb, char *dst_base, i
     if (sv[u] >= 0) __builtin_nontemporal_store(val[u], &dst[g0 + u * kThreads + threadIdx.x]);
 }
 
+// All subnets at once (row-block jobs): a group of 256 central vectors is read ONCE and written to every subnet whose
+// blueprint row names its unit (owners found through the inverse table, scalar loads), instead of once per subnet.
+template <int ES, int TU>
+__device__ __forceinline__ void push_rows(const MoveLaunch &ml, const MoveJob &jb, int lb) {
+  using V = typename VecOf<ES>::vec;
+  constexpr int VN = VecOf<ES>::N;
+  const int qv = jb.Q / VN;
+  const int64_t Wf = (int64_t)jb.n_full * qv;  // a multiple of 256: a group is entirely inside or outside
+  const V *full = reinterpret_cast<const V *>(jb.full);
+  const int64_t g0 = (int64_t)lb * (kThreads * TU);
+  V val[TU];
+#pragma unroll
+  for (int u = 0; u < TU; ++u)
+    if (g0 + u * kThreads < Wf) val[u] = __builtin_nontemporal_load(&full[g0 + u * kThreads + threadIdx.x]);
+#pragma unroll
+  for (int u = 0; u < TU; ++u) {
+    const int64_t g = g0 + u * kThreads;
+    if (g >= Wf) continue;
+    const int unit = __builtin_amdgcn_readfirstlane((int)(g / qv));
+    const int64_t j = g - (int64_t)unit * qv + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      if (i < ml.n_subs) {
+        const int p = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+        if (p >= 0) {
+          V *dst = reinterpret_cast<V *>(const_cast<char *>(ml.sub_base[i]) + jb.sub_off * ES);
+          __builtin_nontemporal_store(val[u], &dst[(int64_t)p * qv + j]);
+        }
+      }
+  }
+}
+
+template <int ES, int TU>
+__global__ __launch_bounds__(kThreads) void extract_all_rows_kernel(const MoveLaunch ml) {
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  push_rows<ES, TU>(ml, jb, blockIdx.x - jb.blk_begin);
+}
+
 template <int ES>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const MoveLaunch ml) {
   const int ji = find_job(ml, blockIdx.x);
@@ -226,7 +266,6 @@ template <int ES> __device__ __forceinline__ typename VecOf<ES>::elem f32_to_ele
 template <> __device__ __forceinline__ uint16_t f32_to_elem<2>(float f) { return (uint16_t)f32_to_bf16(f); }
 template <> __device__ __forceinline__ uint32_t f32_to_elem<4>(float f) { return __float_as_uint(f); }
 
-constexpr int kChunk = 8;  // subnets whose loads are issued together
 
 // Vector path of the pull.  Three phases so that the two dependent memory round trips (inverse table, then
 // data) are each paid once per thread, not once per vector: all table lookups, then all data loads, then the
@@ -580,6 +619,14 @@ twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int tota
   if (total_blocks <= 0) return TWIST_OK;
   if (ctx->esize() == 2) hipLaunchKernelGGL(extract_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   else hipLaunchKernelGGL(extract_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  TW_HIP(ctx, hipGetLastError());
+  return TWIST_OK;
+}
+
+twist_status twist_launch_extract_all(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks) {  // row-block jobs, tile_u = 2
+  if (total_blocks <= 0) return TWIST_OK;
+  if (ctx->esize() == 2) hipLaunchKernelGGL((extract_all_rows_kernel<2, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  else hipLaunchKernelGGL((extract_all_rows_kernel<4, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }

@@ -126,6 +126,8 @@ struct MoveLaunch {
 
 twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
 twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
+// extract of sub_row[0..n_subs) at once into sub_base[0..n_subs): row-block jobs only, described as for the aggregate
+twist_status twist_launch_extract_all(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
 // Running-sum aggregate: add subnet sub_base[0] (blueprint row sub_row[0]; rows sub_row[1..n_subs) were added before it)
 // into the fp32 image, or (finish) write image / owner count over all rows sub_row[0..n_subs) to the central tensors.
 constexpr int kAccumPerBlock = 256 * 4;  // vectors (or elements) of the central tensor one workgroup covers

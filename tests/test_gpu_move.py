@@ -106,6 +106,24 @@ def test_extract_is_a_bit_exact_gather(lib, name):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+def test_extract_all_equals_the_per_subnet_extract_bit_for_bit(lib, name):
+    """twist_extract_all (one pass over the central model for all subnets) against twist_extract, whole slabs compared."""
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=12)
+    for store in (lib.STORE_PARAMS, lib.STORE_GRADS):
+        nb = ctx.twist_subnet_bytes(plan, store)
+        marks = [torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda") for _ in range(S)]   # same filler in both, so padding compares too
+        both = ctx.twist_extract_all(plan, fw, store=store, storages=marks)
+        for s in range(S):
+            one = ctx.twist_extract(plan, fw, s, store=store, storage=torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda"))
+            assert torch.equal(one.storage, both[s].storage), (name, store, s)
+    want = omove.extract(full_np, oplan, S - 1, cfg.d_head, cfg.ffn_granule)      # and against the checker directly
+    got = subnet_to_numpy(both[S - 1], cfg)
+    for l in range(cfg.n_layers):
+        for k, w in want["layers"][l].items():
+            assert np.array_equal(got["layers"][l][k], w), (name, l, k)
+
+
 def _perturb(cfg, sub, s, seed=5):
     """Stand-in for local training: add N(0, 1e-3) noise to every subnet tensor, same on both sides."""
     pert = {}
