@@ -73,6 +73,9 @@ SMALL = {
     "ragged_f32": (si.ModelCfg(n_layers=2, d_model=36, n_heads=5, d_head=6, d_ff=70, ffn_granule=7, vocab=19, max_seq=8), 3, 2, 4),
     "ragged_bf16": (si.ModelCfg(n_layers=1, d_model=100, n_heads=3, d_head=10, d_ff=99, ffn_granule=1, vocab=0, dtype="bf16"), 2, 2, 60),
 }
+# nine subnets: one more than the one-pass kernels handle at once (twist_extract_all falls back to per-subnet gathers,
+# twist_aggregate to its chunked general kernel)
+SMALL["gpt_S9_bf16"] = (replace(si.CFG2, n_layers=1, d_model=256, n_heads=12, d_head=64, d_ff=1024, vocab=300, max_seq=32), 9, 2, 128)
 # the same shapes with the output projections stored unit-major (every partitioned tensor cut along rows)
 for _k in ("cfg1_f32", "gpt_bf16", "llama_bf16", "llama_overlap_S8", "ragged_f32", "ragged_bf16"):
     SMALL[_k + "_um"] = (replace(SMALL[_k][0], out_unit_major=True),) + SMALL[_k][1:]
