@@ -176,6 +176,25 @@ def bench_train(args, tw, si, torch):
     }
     pb, pn = bytes_fwd_bwd_projections(cfg, hs, fs, B, N)
     res["gemm"]["algorithmic_bytes_per_launch"] = pb / pn
+    if args.native_round:
+        # the same round through twist_round: the loop runs inside the library, ONE subnet is resident at a time and the
+        # aggregation is the running fp32 sum (Section 3's round with the repartition interval of Section 5)
+        optd = {"kind": tw.OPT_ADAMW, "lr": 1e-4, "weight_decay": 0.01}
+        sb, wb, ib = ctx.twist_round_bytes(S, hs, fs, B, N, args.local_steps, opt=optd)
+        image = torch.empty(ib, dtype=torch.uint8, device="cuda")
+        x_all = torch.stack(xs).view(S, args.local_steps, B, N).contiguous()
+        y_all = torch.stack(ys).view(S, args.local_steps, B, N).contiguous()
+        losses = torch.zeros(S, args.local_steps, device="cuda")
+        ctx.twist_round(fw, x_all, y_all, S, hs, fs, stor[0], ws, image, losses, seed=0, rnd=100, opt=optd)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(args.steps):
+            ctx.twist_round(fw, x_all, y_all, S, hs, fs, stor[0], ws, image, losses, seed=0, rnd=101 + r, opt=optd)
+        torch.cuda.synchronize()
+        dtn = time.perf_counter() - t0
+        res["native_round"] = {"tokens_per_s": tokens / dtn, "ms_per_round": dtn * 1e3 / args.steps, "resident_subnets": 1,
+                               "running_sum_image_GiB": ib / 2**30, "last_loss": float(losses[-1, -1])}
+        del image
     del stor, ws, layers, globs, fw
     torch.cuda.empty_cache()
     return res
@@ -455,6 +474,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-movers", action="store_true")
     ap.add_argument("--skip-golden", action="store_true", help="skip the pruned-versus-unpruned 7B-shaped forward+backward leg")
+    ap.add_argument("--native-round", action="store_true", help="also time the same round through twist_round (library-side loop, one subnet resident)")
     ap.add_argument("--skip-clock", action="store_true", help="skip the rocm-smi clock reading under projection load")
     ap.add_argument("--ablation", action="store_true", help="also run the GPT-2-small-shaped latency study (kept blocks 10/8/6/4 of 12)")
     ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream also in the timed region (for per-kernel profiles)")
@@ -507,6 +527,7 @@ def main():
         "fwd_bwd": {"tokens_per_s": train["fwd_bwd_tokens_per_s"], "ms": train["fwd_bwd_ms"], "tflops": train["fwd_bwd_tflops"],
                     "frac_mfma_peak": train["fwd_bwd_frac_mfma_peak"]},
         "phase_ms_per_step": train["phase_ms_per_step"],
+        **({"native_round": train["native_round"]} if "native_round" in train else {}),
         "cpu_baseline": cpu,
     }
     if movers:
