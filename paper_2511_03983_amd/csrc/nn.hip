@@ -568,6 +568,27 @@ __global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u3
   a[i] = pack8(o);
 }
 
+// ungated activations (GELU, ReLU), eight values per thread
+__global__ __launch_bounds__(kT) void act_fwd_vec_kernel(int act, const u32x4v *u, u32x4v *a, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const F8 x = unpack8(u[i]);
+  F8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.v[e] = act == TWIST_ACT_RELU ? fmaxf(x.v[e], 0.f) : gelu_tanh(x.v[e]);
+  a[i] = pack8(o);
+}
+
+__global__ __launch_bounds__(kT) void act_bwd_vec_kernel(int act, const u32x4v *u, const u32x4v *da, u32x4v *du, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= total) return;
+  const F8 x = unpack8(u[i]), d = unpack8(da[i]);
+  F8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.v[e] = d.v[e] * (act == TWIST_ACT_RELU ? (x.v[e] > 0.f ? 1.f : 0.f) : gelu_tanh_grad(x.v[e]));
+  du[i] = pack8(o);
+}
+
 __global__ __launch_bounds__(kT) void swiglu_bwd_vec_kernel(const u32x4v *gu, const u32x4v *da, u32x4v *dgu, int F8n, int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
@@ -831,6 +852,11 @@ twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, vo
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
+  if (bf16 && act != TWIST_ACT_SWIGLU && total % 8 == 0 && al16(gu) && al16(a)) {
+    hipLaunchKernelGGL(act_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, act, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), total / 8);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   LAUNCH_BF(act_fwd_kernel, bf16, grid1(total), dim3(kT), act, gu, a, F, total);
   return TWIST_OK;
 }
@@ -840,6 +866,12 @@ twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, co
   if (bf16 && act == TWIST_ACT_SWIGLU && F % 8 == 0 && al16(gu) && al16(da) && al16(dgu)) {
     hipLaunchKernelGGL(swiglu_bwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<const u32x4v *>(da),
                        static_cast<u32x4v *>(dgu), F / 8, total / 8);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
+  if (bf16 && act != TWIST_ACT_SWIGLU && total % 8 == 0 && al16(gu) && al16(da) && al16(dgu)) {
+    hipLaunchKernelGGL(act_bwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, act, static_cast<const u32x4v *>(gu), static_cast<const u32x4v *>(da),
+                       static_cast<u32x4v *>(dgu), total / 8);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
