@@ -51,6 +51,37 @@ def test_sample_matches_oracle_bit_exactly(lib, case):
         plan.close()
 
 
+def test_sample_matches_oracle_on_a_seeded_sweep_of_settings(lib):
+    """Sixty seeded settings of Algorithm 1 (sizes, subnet counts, common sets, coverage on and off, shared layers),
+    every table bit for bit against the checker."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 60:
+        H, U = int(rng.integers(1, 20)), int(rng.integers(1, 70))
+        S = int(rng.integers(1, 9))
+        hs, fs = int(rng.integers(1, H + 1)), int(rng.integers(1, U + 1))
+        ch = tuple(sorted(rng.choice(H, size=int(rng.integers(0, min(hs, 3) + 1)), replace=False).tolist()))
+        cf = tuple(sorted(rng.choice(U, size=int(rng.integers(0, min(fs, 4) + 1)), replace=False).tolist()))
+        cov = bool(rng.integers(0, 2))
+        if cov and (H - len(ch) > S * (hs - len(ch)) or U - len(cf) > S * (fs - len(cf))):
+            continue                                  # violates the size bound below Algorithm 1: covered elsewhere
+        L = int(rng.integers(1, 4))
+        shared = [int(x) for x in rng.integers(0, 2, size=L)] if rng.integers(0, 2) else None
+        seed, rnd = int(rng.integers(0, 2**31)), int(rng.integers(0, 50))
+        cfg = si.ModelCfg(n_layers=L, d_model=16, n_heads=H, d_head=8, d_ff=U * 2, ffn_granule=2, vocab=0)
+        ctx = _ctx(lib, cfg)
+        plan = ctx.twist_sample(S, hs, fs, seed=seed, rnd=rnd, common_heads=ch, common_ffn=cf, layer_shared=shared, require_coverage=cov)
+        want = sample_plan(L, H, U, S, hs, fs, seed, rnd, ch, cf, shared, cov)
+        for l in range(L):
+            for kind in (0, 1):
+                idx, inv, cnt = plan.twist_plan_view(l, kind)
+                w = want[l][kind]
+                assert idx.tolist() == w["idx"] and inv.tolist() == w["inv"] and cnt.tolist() == w["count"], (done, l, kind, H, U, S, hs, fs, ch, cf, cov)
+        plan.close()
+        ctx.close()
+        done += 1
+
+
 def test_sample_rejects_bound_violations(lib):
     ctx = _ctx(lib, si.CFG1)
     with pytest.raises(lib.TwistError) as e:
