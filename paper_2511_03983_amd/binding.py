@@ -337,7 +337,8 @@ class Subnet:
         n = shape[0] * shape[1]
         off = dev.value - self.storage.data_ptr()
         v = self.storage[off: off + n * dt.itemsize].view(dt)
-        return v.view(shape[0], shape[1]) if shape[1] > 1 else v
+        is_matrix = names[t] in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "tok_embed", "pos_embed", "lm_head")
+        return v.view(shape[0], shape[1]) if (shape[1] > 1 or is_matrix) else v      # a one-column matrix stays a matrix
 
     def has(self, layer: int, tensor: str) -> bool:
         try:

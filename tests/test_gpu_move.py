@@ -254,6 +254,61 @@ def test_running_sum_aggregate_equals_the_one_shot_aggregate_bit_for_bit(lib, na
     acc.close()
 
 
+def test_movers_on_a_seeded_sweep_of_ragged_shapes(lib):
+    """Twenty-four seeded small models with awkward sizes (odd widths, granules, subnet counts up to 9, both dtypes, both
+    layouts): extract and extract_all bit for bit against the checker, aggregate within tolerance, and the running-sum
+    aggregate bit for bit against the one-shot aggregate."""
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        H, dh = int(rng.integers(1, 8)), int(rng.choice([2, 6, 8, 10, 16, 24, 32]))
+        g = int(rng.choice([1, 1, 2, 3, 8]))
+        U = int(rng.integers(2, 40))
+        S = int(rng.integers(1, 10))
+        hs, fs = int(rng.integers(max(1, -(-H // S)), H + 1)), int(rng.integers(max(1, -(-U // S)), U + 1))
+        cfg = si.ModelCfg(n_layers=int(rng.integers(1, 3)), d_model=int(rng.choice([8, 12, 36, 64, 100, 256])), n_heads=H, d_head=dh, d_ff=U * g,
+                          ffn_granule=g, vocab=int(rng.choice([0, 37])), max_seq=8, dtype=str(rng.choice(["f32", "bf16"])),
+                          out_unit_major=bool(rng.integers(0, 2)))
+        tag = (case, H, dh, g, U, S, hs, fs, cfg.d_model, cfg.dtype, cfg.out_unit_major, cfg.vocab)
+        full_np = si.make_weights(cfg, 100 + case, generic=True)
+        full_t, other_t = to_device(full_np, cfg), to_device(full_np, cfg)
+        ctx = _ctx(lib, cfg)
+        plan = ctx.twist_sample(S, hs, fs, seed=case)
+        oplan = sample_plan(cfg.n_layers, H, U, S, hs, fs, case)
+        fw, fw2 = lib.FullWeights(full_t["layers"], full_t["globals"]), lib.FullWeights(other_t["layers"], other_t["globals"])
+        subs = ctx.twist_extract_all(plan, fw)
+        for s in range(S):
+            want = omove.extract(full_np, oplan, s, dh, g)
+            got = subnet_to_numpy(subs[s], cfg)
+            one = subnet_to_numpy(ctx.twist_extract(plan, fw, s), cfg)
+            for l in range(cfg.n_layers):
+                for k, w in want["layers"][l].items():
+                    assert np.array_equal(got["layers"][l][k], w) and np.array_equal(one["layers"][l][k], w), (tag, s, l, k)
+            for k, w in want["globals"].items():
+                assert np.array_equal(got["globals"][k], w), (tag, s, k)
+        for s, sub in enumerate(subs):
+            _perturb(cfg, sub, s, seed=case)
+        use = list(range(S))[::-1] if case % 3 == 0 else list(range(S))
+        if case % 4 == 1 and S > 1:
+            use = use[1:]
+        want = omove.aggregate(full_np, oplan, {s: subnet_to_numpy(subs[s], cfg) for s in use}, dh, g)
+        ctx.twist_aggregate(plan, [subs[s] for s in use], fw)
+        acc = ctx.twist_aggregate_begin(plan)
+        for s in use:
+            acc.twist_aggregate_add(subs[s])
+        acc.twist_aggregate_finish(fw2)
+        got = model_to_numpy(full_t, cfg)
+        tol = 5e-3 if cfg.dtype == "bf16" else 1e-4
+        for l in range(cfg.n_layers):
+            for k, w in want["layers"][l].items():
+                assert rel_fro(got["layers"][l][k], w) <= tol, (tag, l, k)
+                assert torch.equal(full_t["layers"][l][k].view(torch.uint8), other_t["layers"][l][k].view(torch.uint8)), (tag, l, k)
+        for k, w in want["globals"].items():
+            assert rel_fro(got["globals"][k], w) <= tol, (tag, k)
+            assert torch.equal(full_t["globals"][k].view(torch.uint8), other_t["globals"][k].view(torch.uint8)), (tag, k)
+        acc.close()
+        ctx.close()
+
+
 def test_untrained_partition_roundtrip_is_bit_exact(lib):
     cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, "gpt_bf16", seed=6)     # 12 = 4*3 heads, 3072 = 4*768
     before = model_to_numpy(full_t, cfg)
