@@ -51,6 +51,27 @@ CASES = {
     "gpt_bf16_bigvocab": (replace(si.CFG2, n_layers=1, d_model=64, n_heads=2, d_head=32, d_ff=128, vocab=33001, max_seq=32), 2, 1, 64, 2, 32),
     "block_llama_bf16": (replace(si.CFG4, n_layers=1, d_model=256, n_heads=4, d_head=64, d_ff=512, max_seq=128), 2, 2, 256, 2, 128),
 }
+# a seeded sweep of bf16 models with awkward widths (projection edges, attention with and without the tiled kernels)
+def _sweep_cases(n=8):
+    rng = np.random.default_rng(31)
+    out = {}
+    for i in range(n):
+        llama = bool(rng.integers(0, 2))
+        dh = int(rng.choice([32, 64, 128]))
+        H = int(rng.integers(2, 6))
+        d = int(rng.choice([64, 136, 192, 264]))
+        F = int(rng.choice([176, 200, 328, 520]))
+        S = 2
+        hs, fs = int(rng.integers(-(-H // S), H + 1)), int(rng.integers(F // 2, F + 1)) // 8 * 8
+        N = int(rng.choice([40, 128, 136, 256]))
+        base = si.CFG3 if llama else si.CFG2
+        cfg = replace(base, n_layers=int(rng.integers(1, 3)), d_model=d, n_heads=H, d_head=dh, d_ff=F, vocab=int(rng.choice([211, 515, 1001])),
+                      max_seq=N, out_unit_major=bool(rng.integers(0, 2)))
+        out[f"sweep{i}_{'llama' if llama else 'gpt'}_d{d}_h{H}x{dh}_f{F}_n{N}"] = (cfg, S, hs, fs, int(rng.integers(1, 3)), N)
+    return out
+
+
+CASES.update(_sweep_cases())
 # the same models with the output projections stored unit-major (their three projections change form)
 for _k in ("gpt_f32", "llama_f32", "gpt_bf16", "llama_bf16"):
     CASES[_k + "_um"] = (replace(CASES[_k][0], out_unit_major=True),) + CASES[_k][1:]
