@@ -357,6 +357,59 @@ def test_round_and_running_aggregate_reject_bad_arguments(lib):
     acc.close()
 
 
+def test_forward_backward_can_be_captured_in_a_graph_and_replayed(lib):
+    """twist_subnet_fwd_bwd + an SGD step recorded once into a HIP graph (both of the library's streams, no allocation,
+    no synchronisation inside) and replayed three times with eager work in between: every replay gives the loss and the
+    weights of the same steps run eagerly."""
+    cfg, S, hs, fs, B, N = CASES["llama_bf16"]
+    full_np = si.make_weights(cfg, 3, std=0.02, generic=True)
+    x_np, y_np, x, y = _data(cfg, B, N, 5)
+    stream = torch.cuda.Stream()
+    results = {}
+    for mode in ("eager", "graph"):
+        full_t = to_device(full_np, cfg)
+        with torch.cuda.stream(stream):
+            ctx = lib.Context(lib.desc_from_cfg(cfg))            # its work goes to `stream`
+            plan = ctx.twist_sample(S, hs, fs, seed=4)
+            fw = lib.FullWeights(full_t["layers"], full_t["globals"])
+            sub = ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS)
+            ws = torch.empty(ctx.twist_workspace_bytes(sub, B, N), dtype=torch.uint8, device="cuda")
+            loss = torch.zeros(1, device="cuda")
+            losses = []
+
+            def step():
+                ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+                ctx.twist_subnet_step(sub, lib.OPT_SGD, lr=1e-2)
+
+            step()                                               # first call creates the library's second stream and events
+            stream.synchronize()
+            losses.append(loss.item())
+            if mode == "graph":
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    step()
+                # (capturing records the step without running it)
+            for it in range(3):
+                if mode == "graph":
+                    g.replay()
+                else:
+                    step()
+                stream.synchronize()
+                losses.append(loss.item())
+                junk = torch.randn(1 << 20, device="cuda").sum().item()      # the program's own eager work between replays
+            results[mode] = (losses, subnet_to_numpy(sub, cfg))
+    assert results["eager"][0] == results["graph"][0], (results["eager"][0], results["graph"][0])
+    assert results["eager"][0][3] < results["eager"][0][0]           # three more SGD steps on one batch: the loss went down
+    for l in range(cfg.n_layers):
+        for k, w in results["eager"][1]["layers"][l].items():
+            assert np.array_equal(w, results["graph"][1]["layers"][l][k]), (l, k)
+    for k, w in results["eager"][1]["globals"].items():
+        if k == "tok_embed":       # its gradient is summed with floating-point atomics: last bits depend on the order
+            assert rel_fro(results["graph"][1]["globals"][k], w) <= 1e-6
+        else:
+            assert np.array_equal(w, results["graph"][1]["globals"][k]), k
+
+
 def test_work_is_enqueued_on_the_contexts_stream(lib):
     """A context created on a non-default stream gives the same bits as one on the default stream (every kernel,
     the second stream's included, is ordered on the stream the caller handed over)."""
