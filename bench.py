@@ -103,6 +103,7 @@ def bench_train(args, tw, si, torch):
     loss = torch.zeros(1, device="cuda")
     ev = lambda: torch.cuda.Event(enable_timing=True)
     phase_ms = {"sample": 0.0, "extract": 0.0, "fwd_bwd": 0.0, "opt_step": 0.0, "aggregate": 0.0}
+    fb_each = []   # each timed forward+backward launch, ms
 
     def one_round(rnd, timed):
         marks = []
@@ -130,7 +131,10 @@ def bench_train(args, tw, si, torch):
         if timed:
             phase_ms["sample"] += t_sample
             for k, x, y in marks:
-                phase_ms[k] += x.elapsed_time(y)
+                t = x.elapsed_time(y)
+                phase_ms[k] += t
+                if k == "fwd_bwd":
+                    fb_each.append(t)
         for sub in subs:
             sub.close()
         plan.close()
@@ -167,7 +171,8 @@ def bench_train(args, tw, si, torch):
     alg = flops_fwd_bwd(cfg, hs, fs, B, N)
     res = {
         "tokens_per_s": tokens / dt, "ms_per_step": dt * 1e3 / args.steps,
-        "fwd_bwd_ms": fb_ms, "fwd_bwd_tokens_per_s": B * N / (fb_ms * 1e-3),
+        "fwd_bwd_ms": fb_ms, "fwd_bwd_median_ms": sorted(fb_each)[len(fb_each) // 2], "fwd_bwd_min_ms": min(fb_each), "fwd_bwd_timed_calls": len(fb_each),
+        "fwd_bwd_tokens_per_s": B * N / (fb_ms * 1e-3),
         "fwd_bwd_tflops": alg / (fb_ms * 1e-3) / 1e12, "fwd_bwd_frac_mfma_peak": alg / (fb_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "phase_ms_per_step": {k: v / args.steps for k, v in phase_ms.items()},
         "gemm": {"launches": n_gemm, "avg_ms": gemm_ms / max(n_gemm, 1), "tflops": gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
@@ -221,8 +226,8 @@ def bench_movers(args, tw, si, torch, unit_major=True):
     image = torch.empty(ctx.twist_aggregate_image_bytes(), dtype=torch.uint8, device="cuda")
     # running-sum form: per added element read 2 B + write 4 B (+ read 4 B unless first owner); finish reads 4 B, writes 2 B
     rs_bytes = (2 + 4) * S * (kept + shared) + 4 * (S * (kept + shared) - (part + shared)) + (4 + 2) * (part + shared)
-    reps = max(3, args.steps)
-    for it in range(2 + reps):
+    warm, reps = 3, max(10, args.steps)
+    for it in range(warm + reps):
         a = ev(); a.record()
         subs = [ctx.twist_extract(plan, fw, s, storage=stor[s]) for s in range(S)]
         b = ev(); b.record()
@@ -247,7 +252,7 @@ def bench_movers(args, tw, si, torch, unit_major=True):
         acc.close()
         for sb in subs_all:
             sb.close()
-        if it >= 2:
+        if it >= warm:
             xa_ms.append(f0.elapsed_time(f1))
             ex_ms.append(a.elapsed_time(b)); ag_ms.append(c0.elapsed_time(d)); rs_ms.append(d.elapsed_time(e))
     n_launch_ex = S * (cfg.n_layers + 0)
@@ -259,7 +264,8 @@ def bench_movers(args, tw, si, torch, unit_major=True):
            "extract_all_moved_GB": (2 * (part + shared) + 2 * (kept + shared) * S) / 1e9,
            "extract_all_GBps_moved": (2 * (part + shared) + 2 * (kept + shared) * S) / med(xa_ms) / 1e6,
            "running_sum_aggregate_ms": med(rs_ms), "running_sum_aggregate_GBps": rs_bytes / med(rs_ms) / 1e6, "running_sum_alg_GB": rs_bytes / 1e9,
-           "extract_launches": n_launch_ex, "aggregate_launches": cfg.n_layers,
+           "extract_launches": n_launch_ex, "aggregate_launches": cfg.n_layers, "warmup": warm, "timed_reps": reps,
+           "extract_min_ms": min(ex_ms), "aggregate_min_ms": min(ag_ms), "extract_all_min_ms": min(xa_ms), "running_sum_aggregate_min_ms": min(rs_ms),
            "extract_frac_hbm_peak": ex_bytes / med(ex_ms) / 1e6 / PEAK_HBM_GBS, "aggregate_frac_hbm_peak": ag_bytes / med(ag_ms) / 1e6 / PEAK_HBM_GBS}
     # plain device copy of known size, the practical ceiling the fractions should be read against
     x = torch.empty(4 << 30, dtype=torch.uint8, device="cuda"); y = torch.empty_like(x)
