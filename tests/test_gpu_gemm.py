@@ -12,7 +12,7 @@ from helpers import rel_fro, to_numpy
 pytestmark = pytest.mark.gpu
 
 SHAPES = [  # (M, N, K): several tiles with ragged edges, a tiny one, k not a multiple of the k-tile
-    (300, 200, 136), (129, 257, 64), (8, 8, 8), (513, 384, 1000), (256, 256, 4096), (1000, 72, 520),
+    (300, 200, 136), (129, 257, 64), (8, 8, 8), (513, 384, 1000), (256, 256, 4096), (1000, 72, 520), (260, 580, 72),
 ]
 
 
