@@ -142,8 +142,9 @@ TWIST_API const char *twist_last_error(const twist_ctx *ctx);
 /* Subnet generator, Algorithm 1 (Section 3.1): one blueprint A (S x N_sub, rows sorted) per layer and
  * block kind, each from its own random stream keyed by (seed, round, layer, kind); plus, derived from A,
  * inv[s][u] = position of block u in row s or -1, and count[u] = number of rows holding u (the denominator
- * of the aggregation formula, Section 3.3).  Host integer work; the tables are also uploaded to the device
- * (synchronous copy).  TWIST_ECONSTRAINT unless |C| <= N_sub <= N_full and, with require_coverage,
+ * of the aggregation formula, Section 3.3).  Host integer work, spread over up to 8 host threads for large models
+ * (the streams are independent, so the tables do not depend on the thread count); the tables are also uploaded to
+ * the device (synchronous copy).  TWIST_ECONSTRAINT unless |C| <= N_sub <= N_full and, with require_coverage,
  * N_full - |C| <= S (N_sub - |C|)  (the bound stated below Algorithm 1). */
 TWIST_API twist_status twist_sample(twist_ctx *ctx, const twist_sample_desc *desc, twist_plan **out);
 /* Borrowed views of one blueprint: idx [S][n_sub], inv [S][n_full], count [n_full], int32, host or device

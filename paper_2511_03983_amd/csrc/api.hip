@@ -3,7 +3,9 @@
 // Section 3.3) launch.
 #include <algorithm>
 #include <cstring>
+#include <atomic>
 #include <new>
+#include <thread>
 
 #include "twist_internal.h"
 
@@ -78,9 +80,8 @@ struct DrawStream {
   }
 };
 
-// Algorithm 1.  rows[s] receives subnet s's sorted block ids.
-twist_status generate_blueprint(twist_ctx *ctx, int n_full, int S, int n_sub, const int32_t *common, int n_common,
-                                bool require_coverage, DrawStream &rng, std::vector<int32_t> &idx) {
+// Argument checks of Algorithm 1 (the same for every layer of one kind, so they run once, before any drawing).
+twist_status check_blueprint_args(twist_ctx *ctx, int n_full, int S, int n_sub, const int32_t *common, int n_common, bool require_coverage) {
   if (n_common < 0 || (n_common > 0 && !common)) TW_FAIL(ctx, TWIST_EINVAL, "twist_sample: bad common set");
   for (int i = 0; i < n_common; ++i)
     if (common[i] < 0 || common[i] >= n_full || (i > 0 && common[i] <= common[i - 1]))
@@ -90,7 +91,13 @@ twist_status generate_blueprint(twist_ctx *ctx, int n_full, int S, int n_sub, co
   if (require_coverage && (int64_t)n_full - n_common > (int64_t)S * (n_sub - n_common))
     TW_FAIL(ctx, TWIST_ECONSTRAINT, "twist_sample: N_full - |C| = %d exceeds S (N_sub - |C|) = %lld: not every block can be assigned",
             n_full - n_common, (long long)S * (n_sub - n_common));
+  return TWIST_OK;
+}
 
+// Algorithm 1 on checked arguments.  Row s of idx receives subnet s's block ids in ascending order.  Touches nothing
+// but its arguments, so the (layer, kind) entries of a plan can be drawn on separate host threads.
+void generate_blueprint(int n_full, int S, int n_sub, const int32_t *common, int n_common, bool require_coverage, DrawStream &rng,
+                        std::vector<int32_t> &idx) {
   std::vector<uint8_t> is_common(n_full, 0);
   for (int i = 0; i < n_common; ++i) is_common[common[i]] = 1;
   // fill level of each row; the common blocks come first
@@ -116,21 +123,23 @@ twist_status generate_blueprint(twist_ctx *ctx, int n_full, int S, int n_sub, co
   for (int s = 0; s < S; ++s) {
     int32_t *row = idx.data() + (size_t)s * n_sub;
     const int missing = n_sub - fill[s];
+    std::fill(held.begin(), held.end(), 0);
+    for (int k = 0; k < fill[s]; ++k) held[row[k]] = 1;
     if (missing > 0) {
-      std::fill(held.begin(), held.end(), 0);
-      for (int k = 0; k < fill[s]; ++k) held[row[k]] = 1;
       pool.clear();
       for (int b = 0; b < n_full; ++b)
         if (!held[b]) pool.push_back(b);
       for (int t = 0; t < missing; ++t) {
         uint32_t j = t + rng.below((uint32_t)(pool.size() - t));
         std::swap(pool[t], pool[j]);
-        row[fill[s] + t] = pool[t];
+        held[pool[t]] = 1;
       }
     }
-    std::sort(row, row + n_sub);
+    // the row in ascending order: its blocks are distinct, so reading the membership flags in order sorts it
+    int k = 0;
+    for (int b = 0; b < n_full; ++b)
+      if (held[b]) row[k++] = b;
   }
-  return TWIST_OK;
 }
 
 // tensors and how the blueprint cuts them: kind, and whether blocks are rows (0) or columns (1)
@@ -254,36 +263,70 @@ extern "C" twist_status twist_sample(twist_ctx *ctx, const twist_sample_desc *sd
   plan->S = sd->S;
   plan->scale_mode = sd->scale_mode;
   plan->e.resize((size_t)d.n_layers * 2);
-  size_t table_ints = 0;
-  for (int l = 0; l < d.n_layers; ++l) {
-    for (int kind = 0; kind < 2; ++kind) {
-      PlanEntry &pe = plan->e[(size_t)l * 2 + kind];
-      pe.n_full = kind == TWIST_KIND_HEAD ? d.n_heads : ctx->n_ffn_units();
-      const bool shared = sd->layer_shared && sd->layer_shared[l];
-      if (shared) {
-        pe.n_sub = pe.n_full;
-        pe.idx.resize((size_t)sd->S * pe.n_full);
-        for (int s = 0; s < sd->S; ++s)
-          for (int b = 0; b < pe.n_full; ++b) pe.idx[(size_t)s * pe.n_full + b] = b;
-      } else {
-        pe.n_sub = kind == TWIST_KIND_HEAD ? sd->heads_sub : sd->ffn_units_sub;
-        DrawStream rng(sd->seed, sd->round, (uint64_t)l, (uint64_t)kind);
-        twist_status st = generate_blueprint(ctx, pe.n_full, sd->S, pe.n_sub, kind == TWIST_KIND_HEAD ? sd->common_heads : sd->common_ffn,
-                                             kind == TWIST_KIND_HEAD ? sd->n_common_heads : sd->n_common_ffn, sd->require_coverage != 0, rng, pe.idx);
-        if (st != TWIST_OK) { delete plan; return st; }
-      }
-      // inverse positions and owner counts
-      pe.inv.assign((size_t)sd->S * pe.n_full, -1);
-      pe.count.assign(pe.n_full, 0);
+  bool any_drawn = false;  // false when every layer is kept whole
+  for (int l = 0; l < d.n_layers; ++l) any_drawn = any_drawn || !(sd->layer_shared && sd->layer_shared[l]);
+  for (int kind = 0; any_drawn && kind < 2; ++kind) {
+    const bool head = kind == TWIST_KIND_HEAD;
+    twist_status st = check_blueprint_args(ctx, head ? d.n_heads : ctx->n_ffn_units(), sd->S, head ? sd->heads_sub : sd->ffn_units_sub,
+                                           head ? sd->common_heads : sd->common_ffn, head ? sd->n_common_heads : sd->n_common_ffn, sd->require_coverage != 0);
+    if (st != TWIST_OK) { delete plan; return st; }
+  }
+  // Every (layer, kind) entry has a draw stream of its own, so the entries are drawn on a few host threads (entry e
+  // on thread e mod n); the result does not depend on how many there are.
+  const int n_entries = d.n_layers * 2;
+  auto draw_entry = [&](int e) {
+    const int l = e / 2, kind = e % 2;
+    PlanEntry &pe = plan->e[(size_t)e];
+    pe.n_full = kind == TWIST_KIND_HEAD ? d.n_heads : ctx->n_ffn_units();
+    const bool shared = sd->layer_shared && sd->layer_shared[l];
+    if (shared) {
+      pe.n_sub = pe.n_full;
+      pe.idx.resize((size_t)sd->S * pe.n_full);
       for (int s = 0; s < sd->S; ++s)
-        for (int k = 0; k < pe.n_sub; ++k) {
-          int32_t u = pe.idx[(size_t)s * pe.n_sub + k];
-          pe.inv[(size_t)s * pe.n_full + u] = k;
-          pe.count[u] += 1;
-        }
-      table_ints += pe.idx.size() + pe.inv.size() + pe.count.size();
-      table_ints = align_up(table_ints, 64);
+        for (int b = 0; b < pe.n_full; ++b) pe.idx[(size_t)s * pe.n_full + b] = b;
+    } else {
+      pe.n_sub = kind == TWIST_KIND_HEAD ? sd->heads_sub : sd->ffn_units_sub;
+      DrawStream rng(sd->seed, sd->round, (uint64_t)l, (uint64_t)kind);
+      generate_blueprint(pe.n_full, sd->S, pe.n_sub, kind == TWIST_KIND_HEAD ? sd->common_heads : sd->common_ffn,
+                         kind == TWIST_KIND_HEAD ? sd->n_common_heads : sd->n_common_ffn, sd->require_coverage != 0, rng, pe.idx);
     }
+    // inverse positions and owner counts
+    pe.inv.assign((size_t)sd->S * pe.n_full, -1);
+    pe.count.assign(pe.n_full, 0);
+    for (int s = 0; s < sd->S; ++s)
+      for (int k = 0; k < pe.n_sub; ++k) {
+        int32_t u = pe.idx[(size_t)s * pe.n_sub + k];
+        pe.inv[(size_t)s * pe.n_full + u] = k;
+        pe.count[u] += 1;
+      }
+  };
+  // threads only when there is enough to draw to pay for starting them
+  const int64_t draw_work = (int64_t)n_entries * sd->S * ctx->n_ffn_units();
+  const int hw = (int)std::thread::hardware_concurrency();
+  const int n_threads = draw_work < (1 << 18) ? 1 : std::max(1, std::min({8, hw > 0 ? hw : 1, n_entries}));
+  std::atomic<bool> failed{false};
+  auto draw_share = [&](int t) {  // entries t, t + n_threads, ...
+    try {
+      for (int e = t; e < n_entries; e += n_threads) draw_entry(e);
+    } catch (...) {
+      failed = true;  // out of host memory
+    }
+  };
+  std::vector<std::thread> pool;
+  int started = 1;  // share 0 is the calling thread's
+  try {
+    pool.reserve(n_threads);
+    for (; started < n_threads; ++started) pool.emplace_back(draw_share, started);
+  } catch (...) {  // no more threads to be had: the caller draws the remaining shares itself
+  }
+  draw_share(0);
+  for (int t = started; t < n_threads; ++t) draw_share(t);
+  for (std::thread &th : pool) th.join();
+  if (failed) { delete plan; TW_FAIL(ctx, TWIST_ENOMEM, "twist_sample: out of host memory while drawing the blueprints"); }
+  size_t table_ints = 0;
+  for (const PlanEntry &pe : plan->e) {
+    table_ints += pe.idx.size() + pe.inv.size() + pe.count.size();
+    table_ints = align_up(table_ints, 64);
   }
   // one device allocation for all tables
   hipError_t e = hipMalloc(reinterpret_cast<void **>(&plan->d_tables), table_ints * sizeof(int32_t));

@@ -27,6 +27,7 @@ SAMPLE_CASES = [
     (4, 12, 64, 3072, 256, 4, 6, 8, (0, 5), (3,), [1, 0, 0, 1], True),    # blocks of 256 neurons, common sets, shared layers
     (2, 32, 128, 11008, 1, 1, 16, 5504, (), (), None, False),             # deployment: one subnet, no coverage
     (2, 7, 32, 33, 3, 3, 5, 6, (2,), (), None, True),                     # odd sizes
+    (13, 16, 128, 5632, 1, 4, 8, 2816, (1,), (7, 4000), None, True),      # 26 tables: more than the library's host threads
 ]
 
 
