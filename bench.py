@@ -212,6 +212,13 @@ def bench_movers(args, tw, si, torch, unit_major=True):
     layers, _ = device_weights(cfg, 1, si, torch)
     fw = tw.FullWeights(layers)
     ctx = tw.Context(tw.desc_from_cfg(cfg))
+    t_sample = []
+    for r in range(4):   # host time of Algorithm 1 + table upload at this shape (first call untimed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plan = ctx.twist_sample(S, hs, fs, seed=11, rnd=r)
+        t_sample.append((time.perf_counter() - t0) * 1e3)
+        plan.close()
     plan = ctx.twist_sample(S, hs, fs, seed=11)
     nb = ctx.twist_subnet_bytes(plan)
     stor = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(S)]
@@ -264,6 +271,7 @@ def bench_movers(args, tw, si, torch, unit_major=True):
            "extract_all_moved_GB": (2 * (part + shared) + 2 * (kept + shared) * S) / 1e9,
            "extract_all_GBps_moved": (2 * (part + shared) + 2 * (kept + shared) * S) / med(xa_ms) / 1e6,
            "running_sum_aggregate_ms": med(rs_ms), "running_sum_aggregate_GBps": rs_bytes / med(rs_ms) / 1e6, "running_sum_alg_GB": rs_bytes / 1e9,
+           "sample_host_ms": sorted(t_sample[1:])[1],
            "extract_launches": n_launch_ex, "aggregate_launches": cfg.n_layers, "warmup": warm, "timed_reps": reps,
            "extract_min_ms": min(ex_ms), "aggregate_min_ms": min(ag_ms), "extract_all_min_ms": min(xa_ms), "running_sum_aggregate_min_ms": min(rs_ms),
            "extract_frac_hbm_peak": ex_bytes / med(ex_ms) / 1e6 / PEAK_HBM_GBS, "aggregate_frac_hbm_peak": ag_bytes / med(ag_ms) / 1e6 / PEAK_HBM_GBS}
