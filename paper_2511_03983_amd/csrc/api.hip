@@ -442,8 +442,8 @@ twist_status check_full(twist_ctx *ctx, const twist_full_weights *full, const ch
   return TWIST_OK;
 }
 
-// Run `launch` over every layer (and once for the model-level tensors).  A layer's row-block jobs go into one
-// launch and its other jobs into a second one when aggregating (which has a lighter kernel for the former).
+// Run `launch` over every layer (and once for the model-level tensors).  When aggregating, a layer's row-block jobs,
+// its other 16-byte jobs and its element-path jobs go into three launches (each kind has a kernel of its own).
 enum JobFilter { JOBS_ALL = 0, JOBS_ROW_BLOCKS = 1, JOBS_NOT_ROW_BLOCKS = 2 };
 template <class F>
 twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int s, bool for_aggregate, MoveLaunch &ml, F launch,
@@ -451,14 +451,14 @@ twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_
   const twist_model_desc &d = ctx->d;
   for (int l = -1; l < d.n_layers; ++l) {
     const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
-    for (int pass = 0; pass < (for_aggregate ? 2 : 1); ++pass) {
+    for (int pass = 0; pass < (for_aggregate ? 3 : 1); ++pass) {
       ml.n_jobs = 0;
       int blocks = 0;
       for (int t = 0; t < nt; ++t) {
         const void *fp = l < 0 ? full->global_tensors[t] : full->layer_tensors[(size_t)l * TWIST_N_LAYER_TENSORS + t];
         MoveJob &jb = ml.job[ml.n_jobs];
         if (!make_job(ctx, plan, l, t, fp, s, for_aggregate, ml.n_subs, jb)) continue;
-        if (for_aggregate && (jb.vec == 2) != (pass == 0)) continue;
+        if (for_aggregate && jb.vec != 2 - pass) continue;
         if ((filter == JOBS_ROW_BLOCKS && jb.vec != 2) || (filter == JOBS_NOT_ROW_BLOCKS && jb.vec == 2)) continue;
         jb.blk_begin = blocks;
         blocks += job_blocks(jb);

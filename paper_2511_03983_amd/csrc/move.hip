@@ -10,6 +10,8 @@
 // paths: 16-byte vectors when segments are 16-byte multiples (whole matrix rows, head columns), and an
 // element path with lane-consecutive elements (neuron columns of the down projection), where a wave's 64
 // lanes read a short contiguous span of the source row and write one full 128-byte line.
+#include <type_traits>
+
 #include "twist_internal.h"
 
 namespace {
@@ -439,6 +441,192 @@ __device__ __forceinline__ void pull_elem(const MoveLaunch &ml, const MoveJob &j
   }
 }
 
+// Element path of the pull with the subnet rows staged through LDS (at most kChunk subnets).  The blueprint rows are
+// ascending, so the elements a subnet contributes to a tile of 512 adjacent central elements are ADJACENT in its own
+// row: instead of 2-byte loads scattered by the inverse table, each wave copies whole (row, subnet) spans into LDS
+// with aligned 16-byte loads, and the threads then pick their elements out of LDS.  Sums are formed in subnet order
+// as in pull_elem: the accumulator starts at -0.0, which leaves the first owner's value (any value, signed zeros
+// included) unchanged, and a subnet that does not hold the element reads -0.0 from a dummy block behind the spans, so
+// the row loop needs no masks and no branches.  Vector loads start at the 16-byte boundary at or below the span and
+// end at the one at or above it; tensors start on 256-byte boundaries of a slab whose end is padded likewise, so they
+// stay inside the subnet's slab.  A tile whose spans do not fit (never the case for tables made by twist_sample) is
+// read from the subnets directly.  Positions are kept in 32 bits: the caller checks that a subnet row is shorter
+// than 2^31 elements.
+constexpr int kStageRows = 4;  // rows staged per pass: one per wave
+template <int ES> struct StageShape {
+  static constexpr int VN = VecOf<ES>::N;
+  static constexpr int SEGV = 512 / VN + 1;                   // 16-byte vectors per (row, subnet) span: 512 elements + misalignment
+  static constexpr int VECS = kStageRows * kChunk * SEGV + 2; // + the dummy block of -0.0 values (at least VN of them)
+};
+template <int ES>
+__device__ __forceinline__ void pull_elem_staged(const MoveLaunch &ml, const MoveJob &jb, int lb, u32x4 *stage, int *span_lo, int *span_hi) {
+  using E = typename VecOf<ES>::elem;
+  constexpr int VN = StageShape<ES>::VN, SEGV = StageShape<ES>::SEGV, SEG = SEGV * VN;
+  constexpr int DUMMY = kStageRows * kChunk * SEG;  // first element of the dummy block
+  static_assert(kStageRows == kThreads / 64, "one staged row per wave");
+  typedef const E __attribute__((address_space(3))) *lds_elems;
+  typedef const u32x4 __attribute__((address_space(1))) *global_vecs;  // plain global loads: they leave the LDS counter alone
+  const lds_elems stage_e = (lds_elems)stage;
+  const int64_t Ws = (int64_t)jb.n_sub * jb.Q, Wf = (int64_t)jb.n_full * jb.Q;
+  const int ct = lb % jb.tiles_per_row, rt = lb / jb.tiles_per_row;
+  E *full = reinterpret_cast<E *>(const_cast<void *>(jb.full));
+  const int r0 = rt * jb.tile_rows;
+  const int r1 = min(r0 + jb.tile_rows, jb.rows);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // wave-uniform: span arithmetic stays scalar
+  const int64_t v0 = (int64_t)ct * (kThreads * 2) + 2 * threadIdx.x;
+  const bool in = v0 < Wf, two = v0 + 1 < Wf;
+  if (threadIdx.x < kChunk) { span_lo[threadIdx.x] = 0x7fffffff; span_hi[threadIdx.x] = -1; }
+  constexpr uint32_t neg0 = ES == 2 ? 0x80008000u : 0x80000000u;  // -0.0 in every element
+  if (threadIdx.x < 2) stage[kStageRows * kChunk * SEGV + threadIdx.x] = u32x4{neg0, neg0, neg0, neg0};
+  __syncthreads();
+  int pos[kChunk][2];
+  bool ok[kChunk][2];
+  int have[2] = {0, 0};
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {  // all table lookups first, so that they are in flight together
+    const int64_t v = (two || u == 0) ? v0 + u : v0;
+    const int unit = in ? (int)(v / jb.Q) : 0;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      pos[i][u] = -1;
+      if (in && i < ml.n_subs) pos[i][u] = jb.table ? jb.table[(int64_t)ml.sub_row[i] * jb.n_full + unit] : 0;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int64_t v = (two || u == 0) ? v0 + u : v0;
+    const int unit = in ? (int)(v / jb.Q) : 0;
+    const int j = in ? (int)(v - (int64_t)unit * jb.Q) : 0;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      ok[i][u] = pos[i][u] >= 0 && (u == 0 || two);
+      pos[i][u] = ok[i][u] ? pos[i][u] * jb.Q + j : 0;
+      have[u] += ok[i][u] ? 1 : 0;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i) {
+    const int first = ok[i][0] ? pos[i][0] : pos[i][1], last = ok[i][1] ? pos[i][1] : pos[i][0];
+    if (ok[i][0] || ok[i][1]) { atomicMin(&span_lo[i], min(first, last)); atomicMax(&span_hi[i], max(first, last)); }
+  }
+  __syncthreads();
+  // the spans' bounds and the misalignment of each subnet's row 0 span, wave-uniform
+  int lo[kChunk], hi[kChunk];
+  uint32_t mis[kChunk];
+  bool fits = true;
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i) {
+    lo[i] = __builtin_amdgcn_readfirstlane(span_lo[i]);
+    hi[i] = __builtin_amdgcn_readfirstlane(span_hi[i]);
+    fits = fits && (hi[i] < lo[i] || hi[i] - lo[i] < 512);
+    mis[i] = i < ml.n_subs && hi[i] >= lo[i] ? (uint32_t)((reinterpret_cast<uintptr_t>(ml.sub_base[i]) + (uintptr_t)((jb.sub_off + lo[i]) * ES)) & 15) : 0u;
+  }
+  const uint32_t row_bytes = (uint32_t)(Ws * ES) & 15u;  // what a step of one row adds to the misalignment
+  const float c0 = (float)max(have[0], 1), c1 = (float)max(have[1], 1);
+  const bool packed = ES == 2 && have[0] > 0 && have[1] > 0 && (Wf & 1) == 0 && ((reinterpret_cast<uintptr_t>(full) & 3) == 0);
+  if (!fits) {
+#pragma unroll 1
+    for (int row = r0; row < r1; ++row) {
+      float acc[2] = {-0.f, -0.f};
+#pragma unroll 1
+      for (int i = 0; i < ml.n_subs; ++i) {
+        const E *direct = reinterpret_cast<const E *>(ml.sub_base[i] + jb.sub_off * ES) + row * Ws;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) acc[u] += ok[i][u] ? elem_to_f32<ES>(direct[pos[i][u]]) : -0.f;
+      }
+      if (in) {
+        E *d = full + row * Wf + v0;
+        if (have[0]) d[0] = f32_to_elem<ES>(acc[0] / c0);
+        if (have[1]) d[1] = f32_to_elem<ES>(acc[1] / c1);
+      }
+    }
+    return;
+  }
+  // LDS element index of each source inside a staged row, without the row's misalignment; subnets that do not hold
+  // the element point at the dummy block
+  int off[kChunk][2];
+#pragma unroll
+  for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) off[i][u] = ok[i][u] ? i * SEG + pos[i][u] - lo[i] : DUMMY;
+  // Rows of a subnet tensor that are a multiple of 16 bytes apart (the usual case) all have the misalignment of row
+  // 0, which is then folded into the indices once; otherwise it is recomputed for every row.
+  const bool same_shift = row_bytes == 0;
+  if (same_shift) {
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) off[i][u] += ok[i][u] ? (int)(mis[i] / ES) : 0;
+  }
+  auto consume = [&](int row0, auto shift_varies) {  // sums and stores of the staged rows row0 .. row0 + kStageRows - 1
+#pragma unroll
+    for (int r = 0; r < kStageRows; ++r) {
+      const int row = row0 + r;
+      if (row >= r1) break;
+      float acc[2] = {-0.f, -0.f};
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        const int sh = decltype(shift_varies)::value ? (int)(((mis[i] + (uint32_t)row * row_bytes) & 15u) / ES) : 0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) acc[u] += elem_to_f32<ES>(stage_e[r * kChunk * SEG + off[i][u] + sh]);
+      }
+      if (in) {
+        E *d = full + row * Wf + v0;
+        const E o0 = f32_to_elem<ES>(acc[0] / c0), o1 = f32_to_elem<ES>(acc[1] / c1);
+        if (packed) *reinterpret_cast<uint32_t *>(d) = (uint32_t)o0 | ((uint32_t)o1 << 16);
+        else { if (have[0]) d[0] = o0; if (have[1]) d[1] = o1; }
+      }
+    }
+  };
+  // Copy of the spans of rows row0 .. row0 + kStageRows - 1: wave w takes row row0 + w of every subnet.  issue() starts
+  // the loads of each span's first 64 vectors (lanes beyond the span's last vector repeat that vector), commit() puts
+  // them into LDS; the loads of one pass are in flight while the pass before it is summed.  Vectors 64 and up exist only
+  // for spans of (nearly) all 512 elements and are copied by commit() itself.
+  constexpr int SLOTS = (SEGV + 63) / 64;
+  u32x4 buf[kChunk];
+  int nv[kChunk];
+  auto span_start = [&](int i, int row, int &n_vec) -> global_vecs {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(ml.sub_base[i]) + (uintptr_t)((jb.sub_off + row * Ws + lo[i]) * ES);
+    const uintptr_t a0 = a & ~(uintptr_t)15;
+    n_vec = (int)((a - a0) / ES + (hi[i] - lo[i] + 1) + VN - 1) / VN;  // 1 .. SEGV
+    return (global_vecs)a0;
+  };
+  auto issue = [&](int row0) {
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      nv[i] = 0;
+      if (i < ml.n_subs && row0 + wave < r1 && hi[i] >= lo[i]) {
+        const global_vecs src = span_start(i, row0 + wave, nv[i]);
+        buf[i] = __builtin_nontemporal_load(src + min(lane, nv[i] - 1));
+      }
+    }
+  };
+  auto commit = [&](int row0) {
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i)
+      if (nv[i] > 0) {
+        stage[(wave * kChunk + i) * SEGV + min(lane, nv[i] - 1)] = buf[i];
+#pragma unroll
+        for (int k = 1; k < SLOTS; ++k)
+          if (nv[i] > 64 * k) {
+            int n;
+            const global_vecs src = span_start(i, row0 + wave, n);
+            const int idx = min(lane + 64 * k, n - 1);
+            stage[(wave * kChunk + i) * SEGV + idx] = __builtin_nontemporal_load(src + idx);
+          }
+      }
+  };
+  issue(r0);
+  for (int row0 = r0; row0 < r1; row0 += kStageRows) {
+    commit(row0);
+    __syncthreads();
+    if (row0 + kStageRows < r1) issue(row0 + kStageRows);
+    if (same_shift) consume(row0, std::false_type());
+    else consume(row0, std::true_type());
+    __syncthreads();  // the next pass overwrites the staged spans
+  }
+}
+
 // Row-block path of the pull (see gather_rows): the owners of a group of 256 central vectors are found with
 // scalar loads of the inverse table, and only the subnets that hold the unit are read.
 template <int ES, int TU>
@@ -501,6 +689,16 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const MoveLaunch ml
   } else {
     pull_elem<ES>(ml, jb, lb);
   }
+}
+
+// launches that hold element-path jobs only
+template <int ES>
+__global__ __launch_bounds__(kThreads) void aggregate_elem_kernel(const MoveLaunch ml) {
+  __shared__ u32x4 stage[StageShape<ES>::VECS];
+  __shared__ int span_lo[kChunk], span_hi[kChunk];
+  const int ji = find_job(ml, blockIdx.x);
+  const MoveJob &jb = ml.job[ji];
+  pull_elem_staged<ES>(ml, jb, blockIdx.x - jb.blk_begin, stage, span_lo, span_hi);
 }
 
 // launches that hold row-block jobs only: far fewer registers than the general kernel, hence more waves in flight
@@ -635,7 +833,12 @@ twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int to
   if (total_blocks <= 0) return TWIST_OK;
   bool rows_only = true;
   for (int i = 0; i < ml.n_jobs; ++i) rows_only = rows_only && ml.job[i].vec == 2;
-  if (rows_only) {  // the host gives such jobs tile_u = 2
+  bool elems_only = ml.n_subs <= kChunk;  // element-path jobs whose subnet rows are short enough for 32-bit positions
+  for (int i = 0; i < ml.n_jobs; ++i) elems_only = elems_only && ml.job[i].vec == 0 && (int64_t)ml.job[i].n_sub * ml.job[i].Q < (1ll << 31);
+  if (elems_only) {
+    if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_elem_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+    else hipLaunchKernelGGL(aggregate_elem_kernel<4>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
+  } else if (rows_only) {  // the host gives such jobs tile_u = 2
     if (ctx->esize() == 2) hipLaunchKernelGGL((aggregate_rows_kernel<2, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
     else hipLaunchKernelGGL((aggregate_rows_kernel<4, 2>), dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);
   } else if (ctx->esize() == 2) hipLaunchKernelGGL(aggregate_kernel<2>, dim3(total_blocks), dim3(kThreads), 0, ctx->stream, ml);

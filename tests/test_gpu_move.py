@@ -105,6 +105,10 @@ SMALL = {
     "ragged_f32": (si.ModelCfg(n_layers=2, d_model=36, n_heads=5, d_head=6, d_ff=70, ffn_granule=7, vocab=19, max_seq=8), 3, 2, 4),
     "ragged_bf16": (si.ModelCfg(n_layers=1, d_model=100, n_heads=3, d_head=10, d_ff=99, ffn_granule=1, vocab=0, dtype="bf16"), 2, 2, 60),
 }
+# nearly every neuron kept and rows of odd length: the spans of the down projection's element path are as long as a
+# tile allows and start at a different misalignment in every row
+SMALL["wide_odd_bf16"] = (si.ModelCfg(n_layers=1, d_model=40, n_heads=2, d_head=8, d_ff=1101, ffn_granule=1, vocab=0, dtype="bf16"), 2, 1, 1100)
+SMALL["wide_odd_f32"] = (si.ModelCfg(n_layers=1, d_model=24, n_heads=2, d_head=8, d_ff=1101, ffn_granule=1, vocab=0), 3, 2, 1101)
 # nine subnets: one more than the one-pass kernels handle at once (twist_extract_all falls back to per-subnet gathers,
 # twist_aggregate to its chunked general kernel)
 SMALL["gpt_S9_bf16"] = (replace(si.CFG2, n_layers=1, d_model=256, n_heads=12, d_head=64, d_ff=1024, vocab=300, max_seq=32), 9, 2, 128)
