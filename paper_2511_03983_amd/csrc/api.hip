@@ -442,30 +442,39 @@ twist_status check_full(twist_ctx *ctx, const twist_full_weights *full, const ch
   return TWIST_OK;
 }
 
-// Run `launch` over every layer (and once for the model-level tensors).  When aggregating, a layer's row-block jobs,
-// its other 16-byte jobs and its element-path jobs go into three launches (each kind has a kernel of its own).
+// Run `launch` over the model-level tensors and every layer, as many whole layers per launch as the job table holds.
+// When aggregating, the row-block jobs, the other 16-byte jobs and the element-path jobs go into launches of their own
+// (each kind has a kernel of its own).
 enum JobFilter { JOBS_ALL = 0, JOBS_ROW_BLOCKS = 1, JOBS_NOT_ROW_BLOCKS = 2 };
 template <class F>
 twist_status for_each_group(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int s, bool for_aggregate, MoveLaunch &ml, F launch,
                             JobFilter filter = JOBS_ALL) {
   const twist_model_desc &d = ctx->d;
-  for (int l = -1; l < d.n_layers; ++l) {
-    const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
-    for (int pass = 0; pass < (for_aggregate ? 3 : 1); ++pass) {
+  for (int pass = 0; pass < (for_aggregate ? 3 : 1); ++pass) {
+    ml.n_jobs = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> twist_status {
+      twist_status st = ml.n_jobs ? launch(ml, (int)blocks) : TWIST_OK;
       ml.n_jobs = 0;
-      int blocks = 0;
+      blocks = 0;
+      return st;
+    };
+    for (int l = -1; l < d.n_layers; ++l) {
+      const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
+      if (ml.n_jobs + nt > TWIST_MAX_JOBS || blocks > (1 << 30)) TW_TRY(flush());
       for (int t = 0; t < nt; ++t) {
         const void *fp = l < 0 ? full->global_tensors[t] : full->layer_tensors[(size_t)l * TWIST_N_LAYER_TENSORS + t];
         MoveJob &jb = ml.job[ml.n_jobs];
         if (!make_job(ctx, plan, l, t, fp, s, for_aggregate, ml.n_subs, jb)) continue;
         if (for_aggregate && jb.vec != 2 - pass) continue;
         if ((filter == JOBS_ROW_BLOCKS && jb.vec != 2) || (filter == JOBS_NOT_ROW_BLOCKS && jb.vec == 2)) continue;
-        jb.blk_begin = blocks;
+        jb.blk_begin = (int32_t)blocks;
+        ml.blk_begin[ml.n_jobs] = jb.blk_begin;
         blocks += job_blocks(jb);
         ++ml.n_jobs;
       }
-      TW_TRY(launch(ml, blocks));
     }
+    TW_TRY(flush());
   }
   return TWIST_OK;
 }
@@ -645,15 +654,22 @@ int64_t image_layout(const twist_model_desc &d, std::vector<int64_t> *layer_off,
   return n;
 }
 
-// One launch per layer (and one for the model-level tensors) over the central layout.  `full` is null for an add.
+// Launches over the central layout, as many whole layers per launch as the job table holds.  `full` is null for an add.
 twist_status for_each_image_group(twist_accum *acc, const twist_full_weights *full, MoveLaunch &ml, bool finish) {
   twist_ctx *ctx = acc->ctx;
   const twist_model_desc &d = ctx->d;
   const int VN = 16 / ctx->esize();
+  ml.n_jobs = 0;
+  int64_t blocks = 0;
+  auto flush = [&]() -> twist_status {
+    twist_status st = ml.n_jobs ? twist_launch_accumulate(ctx, ml, (int)blocks, finish) : TWIST_OK;
+    ml.n_jobs = 0;
+    blocks = 0;
+    return st;
+  };
   for (int l = -1; l < d.n_layers; ++l) {
     const int nt = l < 0 ? TWIST_N_GLOBAL_TENSORS : TWIST_N_LAYER_TENSORS;
-    ml.n_jobs = 0;
-    int64_t blocks = 0;
+    if (ml.n_jobs + nt > TWIST_MAX_JOBS || blocks > (1 << 30)) TW_TRY(flush());
     for (int t = 0; t < nt; ++t) {
       const int64_t off = l < 0 ? acc->global_off[t] : acc->layer_off[(size_t)l * TWIST_N_LAYER_TENSORS + t];
       if (off < 0) continue;
@@ -666,12 +682,12 @@ twist_status for_each_image_group(twist_accum *acc, const twist_full_weights *fu
       const int64_t total = (int64_t)jb.rows * jb.n_full * (jb.vec ? jb.Q / VN : jb.Q);
       if (total >= (int64_t)1 << 31) TW_FAIL(ctx, TWIST_ESHAPE, "running-sum aggregate: a tensor of %lld vectors exceeds the 32-bit index range", (long long)total);
       jb.blk_begin = (int32_t)blocks;
+      ml.blk_begin[ml.n_jobs] = jb.blk_begin;
       blocks += (total + kAccumPerBlock - 1) / kAccumPerBlock;
       ++ml.n_jobs;
     }
-    TW_TRY(twist_launch_accumulate(ctx, ml, (int)blocks, finish));
   }
-  return TWIST_OK;
+  return flush();
 }
 
 }  // namespace

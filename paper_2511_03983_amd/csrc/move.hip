@@ -38,7 +38,7 @@ __device__ __forceinline__ int find_job(const MoveLaunch &ml, int blk) {
   int j = 0;
 #pragma unroll 1
   for (int i = 1; i < ml.n_jobs; ++i)
-    if (blk >= ml.job[i].blk_begin) j = i;
+    if (blk >= ml.blk_begin[i]) j = i;
   return j;
 }
 

@@ -115,14 +115,20 @@ struct MoveJob {
   float *acc;                 // running-sum aggregate only: fp32 image of the central tensor [rows][n_full*Q]
 };
 
-#define TWIST_MAX_JOBS 20
+// A launch carries the jobs of several layers (as many whole layers as fit): at the 7B shape a layer's extract takes
+// about 70 us, and every launch boundary costs about 10 us of drained GPU.  The struct travels as the kernel argument,
+// which HIP limits to 4 KB.
+#define TWIST_MAX_JOBS 44
 struct MoveLaunch {
   MoveJob job[TWIST_MAX_JOBS];
+  int32_t blk_begin[TWIST_MAX_JOBS];  // copy of job[i].blk_begin, packed so that a workgroup finds its job with few loads
   int32_t n_jobs;
   int32_t n_subs;                 // aggregate only
   const char *sub_base[TWIST_MAX_S];  // aggregate: weight slab of each given subnet; extract: [0] = destination
   int32_t sub_row[TWIST_MAX_S];   // aggregate: blueprint row of each given subnet
 };
+
+static_assert(sizeof(MoveLaunch) <= 4000, "MoveLaunch is passed by value as a kernel argument");
 
 twist_status twist_launch_extract(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
 twist_status twist_launch_aggregate(twist_ctx *ctx, const MoveLaunch &ml, int total_blocks);
