@@ -109,6 +109,9 @@ SMALL = {
 # tile allows and start at a different misalignment in every row
 SMALL["wide_odd_bf16"] = (si.ModelCfg(n_layers=1, d_model=40, n_heads=2, d_head=8, d_ff=1101, ffn_granule=1, vocab=0, dtype="bf16"), 2, 1, 1100)
 SMALL["wide_odd_f32"] = (si.ModelCfg(n_layers=1, d_model=24, n_heads=2, d_head=8, d_ff=1101, ffn_granule=1, vocab=0), 3, 2, 1101)
+# more layers than one launch's job table holds (two such layers fit): the movers cut the model into several launches
+SMALL["gpt_12layers_f32"] = (replace(si.CFG1, n_layers=12, d_model=32, n_heads=4, d_head=8, d_ff=96, vocab=40, max_seq=8), 3, 2, 40)
+SMALL["llama_11layers_bf16"] = (replace(si.CFG3, n_layers=11, d_model=64, n_heads=4, d_head=16, d_ff=136, vocab=50, max_seq=8), 4, 2, 70)
 # nine subnets: one more than the one-pass kernels handle at once (twist_extract_all falls back to per-subnet gathers,
 # twist_aggregate to its chunked general kernel)
 SMALL["gpt_S9_bf16"] = (replace(si.CFG2, n_layers=1, d_model=256, n_heads=12, d_head=64, d_ff=1024, vocab=300, max_seq=32), 9, 2, 128)
