@@ -538,7 +538,8 @@ def main():
                      "traffic": TRAFFIC_PROJECTION_LAUNCH, "traffic_unit": "bytes per launch behind the L2 (rocprofv3 FETCH_SIZE/WRITE_SIZE, calibrated)",
                      "algorithmic_bytes_per_launch": g["algorithmic_bytes_per_launch"],
                      "avg_launch_ms": g["avg_ms"], "launches": g["launches"], "flops_per_launch": g["flops_per_launch"]},
-        "fwd_bwd": {"tokens_per_s": train["fwd_bwd_tokens_per_s"], "ms": train["fwd_bwd_ms"], "tflops": train["fwd_bwd_tflops"],
+        "fwd_bwd": {"tokens_per_s": train["fwd_bwd_tokens_per_s"], "ms": train["fwd_bwd_ms"], "median_ms": train["fwd_bwd_median_ms"],
+                    "min_ms": train["fwd_bwd_min_ms"], "timed_calls": train["fwd_bwd_timed_calls"], "tflops": train["fwd_bwd_tflops"],
                     "frac_mfma_peak": train["fwd_bwd_frac_mfma_peak"]},
         "phase_ms_per_step": train["phase_ms_per_step"],
         **({"native_round": train["native_round"]} if "native_round" in train else {}),
