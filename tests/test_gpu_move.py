@@ -1,4 +1,5 @@
 """GPU parity of twist_sample / twist_extract / twist_aggregate against the CPU checker, through the C ABI."""
+import os
 from dataclasses import replace
 
 import numpy as np
@@ -264,13 +265,15 @@ def test_running_sum_aggregate_equals_the_one_shot_aggregate_bit_for_bit(lib, na
 
 def test_movers_on_a_seeded_sweep_of_ragged_shapes(lib):
     """Twenty-four seeded small models with awkward sizes (odd widths, granules, subnet counts up to 9, both dtypes, both
-    layouts): extract and extract_all bit for bit against the checker, aggregate within tolerance, and the running-sum
+    layouts; every fourth one with a wide FFN cut into single neurons): extract and extract_all bit for bit against the checker, aggregate within tolerance, and the running-sum
     aggregate bit for bit against the one-shot aggregate."""
-    rng = np.random.default_rng(77)
-    for case in range(24):
+    rng = np.random.default_rng(int(os.environ.get("TWIST_SWEEP_SEED", "77")))      # other seeds / more cases for a longer soak
+    for case in range(int(os.environ.get("TWIST_SWEEP_CASES", "24"))):
         H, dh = int(rng.integers(1, 8)), int(rng.choice([2, 6, 8, 10, 16, 24, 32]))
         g = int(rng.choice([1, 1, 2, 3, 8]))
         U = int(rng.integers(2, 40))
+        if case % 4 == 3:        # wide FFN with single-neuron blocks: the element path's spans reach a full tile
+            g, U = 1, int(rng.integers(300, 1300))
         S = int(rng.integers(1, 10))
         hs, fs = int(rng.integers(max(1, -(-H // S)), H + 1)), int(rng.integers(max(1, -(-U // S)), U + 1))
         cfg = si.ModelCfg(n_layers=int(rng.integers(1, 3)), d_model=int(rng.choice([8, 12, 36, 64, 100, 256])), n_heads=H, d_head=dh, d_ff=U * g,

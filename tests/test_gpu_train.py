@@ -14,6 +14,7 @@ the other bit by bit.  The bf16 gates therefore are, per tensor:
   * against the rounding-hook checker: error <= format error + 5e-3   (same bound, other reference point);
   * the loss itself, a single well-conditioned scalar: 5e-3 relative against both.
 """
+import os
 from dataclasses import replace
 
 import numpy as np
@@ -52,8 +53,8 @@ CASES = {
     "block_llama_bf16": (replace(si.CFG4, n_layers=1, d_model=256, n_heads=4, d_head=64, d_ff=512, max_seq=128), 2, 2, 256, 2, 128),
 }
 # a seeded sweep of bf16 models with awkward widths (projection edges, attention with and without the tiled kernels)
-def _sweep_cases(n=8):
-    rng = np.random.default_rng(31)
+def _sweep_cases(n=int(os.environ.get("TWIST_SWEEP_CASES", "8"))):      # other seeds / more cases for a longer soak
+    rng = np.random.default_rng(int(os.environ.get("TWIST_SWEEP_SEED", "31")))
     out = {}
     for i in range(n):
         llama = bool(rng.integers(0, 2))
