@@ -53,7 +53,9 @@ enum { TWIST_NORM_LN = 0, TWIST_NORM_RMS = 1 };                    /* desc.norm 
 enum { TWIST_KIND_HEAD = 0, TWIST_KIND_FFN = 1 };                  /* block kinds       */
 enum { TWIST_SCALE_NONE = 0, TWIST_SCALE_SQRT_RATIO = 1 };         /* sample.scale_mode */
 enum { TWIST_OPT_SGD = 0, TWIST_OPT_ADAMW = 1 };
-enum { TWIST_PARAM = 0, TWIST_GRAD = 1 };                          /* twist_subnet_view `what` */
+/* twist_subnet_view `what`: the weights in desc.dtype; the fp32 gradient; the fp32 weights the optimizer updates (bf16
+ * models: the master copy; fp32 models: the weights themselves); the two fp32 AdamW moment estimates */
+enum { TWIST_PARAM = 0, TWIST_GRAD = 1, TWIST_MASTER = 2, TWIST_ADAM_M = 3, TWIST_ADAM_V = 4 };
 /* storage a subnet needs: weights only; + fp32 gradients (and fp32 master weights for bf16 models);
  * + the two AdamW moment buffers. */
 enum { TWIST_STORE_PARAMS = 0, TWIST_STORE_GRADS = 1, TWIST_STORE_ADAMW = 2 };
@@ -152,6 +154,9 @@ TWIST_API twist_status twist_sample(twist_ctx *ctx, const twist_sample_desc *des
 TWIST_API twist_status twist_plan_view(const twist_plan *plan, int32_t layer, int32_t kind, const int32_t **idx,
                              const int32_t **inv, const int32_t **count, int32_t *n_sub, int32_t *n_full,
                              int32_t on_device);
+/* Copies the DEVICE copies of one blueprint's tables into host arrays of S*n_sub, S*n_full and n_full int32 (any may be
+ * NULL): what the gather and pull kernels actually read.  Synchronous copies. */
+TWIST_API twist_status twist_plan_read_device(const twist_plan *plan, int32_t layer, int32_t kind, int32_t *idx, int32_t *inv, int32_t *count);
 TWIST_API void twist_plan_destroy(twist_plan *plan);
 
 /* Bytes of caller-provided device storage a subnet of this plan needs (same for every s). */
@@ -160,8 +165,10 @@ TWIST_API twist_status twist_subnet_bytes(twist_ctx *ctx, const twist_plan *plan
 /* Dispatcher (Section 3.2): materialise subnet s.  For every partitioned tensor the blocks named by row s
  * of the blueprint are concatenated, in row order, into a smaller dense matrix; shared tensors are copied.
  * `storage` (dev, 256-byte aligned, storage_bytes >= twist_subnet_bytes) receives the subnet and stays
- * owned by the caller; gradient and optimizer regions, if requested, are zeroed and fp32 master weights are
- * initialised from the extracted values.  Inside the subnet W^Q,W^K,W^V are stored as one [3 H' d_head, d]
+ * owned by the caller; fp32 master weights, if requested, are initialised from the extracted values.  The gradient
+ * region is left as it is (twist_subnet_fwd_bwd overwrites every gradient, so gradients are undefined until its first
+ * call) and so are the AdamW moments, which count as zero: a subnet's first twist_subnet_step does not read them.
+ * Inside the subnet W^Q,W^K,W^V are stored as one [3 H' d_head, d]
  * matrix and gate/up as one [2 F', d] matrix; twist_subnet_view hides that. */
 TWIST_API twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, int32_t s,
                            void *storage, size_t storage_bytes, int32_t store, twist_subnet **out);
@@ -173,7 +180,9 @@ TWIST_API twist_status twist_extract(twist_ctx *ctx, const twist_plan *plan, con
 TWIST_API twist_status twist_extract_all(twist_ctx *ctx, const twist_plan *plan, const twist_full_weights *full, void *const *storages,
                                          size_t storage_bytes, int32_t store, twist_subnet **out);
 /* Device pointer and [rows, cols] shape (cols = 1 for vectors) of one subnet tensor; layer = -1 selects the
- * model-level tensors.  what = TWIST_PARAM gives desc.dtype data, TWIST_GRAD the fp32 gradient. */
+ * model-level tensors.  what = TWIST_PARAM gives desc.dtype data, TWIST_GRAD the fp32 gradient, TWIST_MASTER the fp32
+ * weights the optimizer updates, TWIST_ADAM_M / TWIST_ADAM_V the AdamW moments (TWIST_EINVAL before the first step, or
+ * when the subnet was extracted without that storage). */
 TWIST_API twist_status twist_subnet_view(const twist_subnet *sub, int32_t layer, int32_t tensor, int32_t what,
                                void **dev, int64_t shape[2]);
 TWIST_API void twist_subnet_destroy(twist_subnet *sub);
@@ -262,10 +271,40 @@ TWIST_API twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M,
  * dout is not NULL) backward, on a fused activation buffer qkv [B*N, 3*Hs*d_head] (q | k | v, desc.dtype).
  * Outputs: o [B*N, Hs*d_head] (desc.dtype), lse [B, Hs, N] fp32 (log-sum-exp of the scaled scores), and dqkv
  * [B*N, 3*Hs*d_head] from dout [B*N, Hs*d_head].  o32 [B*N, Hs*d_head] fp32 and delta [B, Hs, N] fp32 are
- * caller-provided scratch (o32 receives the unrounded output of bf16 models).  All device pointers, caller-owned;
- * work is enqueued on the ctx's stream.  TWIST_ESHAPE if d_head exceeds 256. */
+ * caller-provided scratch (o32 receives the unrounded output of bf16 models).  keep (dev int32 [Hs], may be NULL) is the
+ * head mask of Masked TwIST (Section 4.1): heads with keep[h] < 0 give zero output and zero gradients.  All device
+ * pointers, caller-owned; work is enqueued on the ctx's stream.  TWIST_ESHAPE if d_head exceeds 256. */
 TWIST_API twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs,
-                                           void *o, float *o32, float *lse, float *delta, void *dqkv);
+                                           void *o, float *o32, float *lse, float *delta, void *dqkv, const int32_t *keep);
+
+/* Kernel-level entry points for tests: the memory-bound steps of twist_subnet_fwd_bwd in isolation, run by the same
+ * kernels, on the ctx's stream.  Shapes and kinds come from the ctx's model description (d_model, d_head, norm, act,
+ * vocab, dtype).  All pointers are device pointers owned by the caller; "dtype" means desc.dtype.
+ *
+ * twist_norm_raw   f_ln of Appendix A.1 (LayerNorm, or RMSNorm for desc.norm = TWIST_NORM_RMS): y [T, d_model] (dtype) from
+ *                  x [T, d_model] (fp32 residual stream), gain w and bias b ([d_model], dtype; b NULL for RMSNorm);
+ *                  stats [2 T] fp32 receives (mean, 1/std) per row.  With dy (dtype) not NULL also the backward half:
+ *                  dx [T, d_model] fp32 (overwritten), dxb (dtype copy of dx, may be NULL), dw and db ([d_model] fp32, db
+ *                  may be NULL); scratch: at least ceil(T / 16) * 2 * d_model floats (TWIST_ESHAPE if smaller).
+ * twist_rope_raw   rotary positions (half-split pairing, desc.rope_theta) applied in place to the q and k heads of a
+ *                  fused [B*N, 3*Hs*d_head] buffer (dtype); sign = +1 forward, -1 the backward rotation; tab: scratch
+ *                  of N * d_head floats (receives the cos/sin table).
+ * twist_act_raw    FFN activation of Appendix A.1 (desc.act): a [T, F] from gu [T, F] (GELU, ReLU) or gu [T, 2F] (gate | up
+ *                  for SwiGLU); with da not NULL also dgu (shape of gu) from da [T, F].  keep (int32, one entry per block
+ *                  of `unit` neurons, may be NULL): blocks with keep[b] < 0 are masked (Section 4.1): a = 0, dgu = 0 there.
+ * twist_ce_raw     mean cross-entropy over T rows of logits [T, ld] (dtype; ld >= vocab, columns beyond vocab are
+ *                  padding): loss (fp32 scalar), rowloss [T] fp32, and logits are overwritten by dLoss/dlogits.
+ * twist_embed_raw  x [B*N, d_model] fp32 = tok_embed[tok] (+ pos_embed[position], pos_embed may be NULL); with dx not NULL
+ *                  also the backward half: dx rows are ADDED into d_tok [vocab, d_model] fp32 (caller clears it) and
+ *                  d_pos [N, d_model] fp32 (overwritten, may be NULL) receives the sum over the batch. */
+TWIST_API twist_status twist_norm_raw(twist_ctx *ctx, const float *x, const void *w, const void *b, int32_t T, void *y, float *stats,
+                                      const void *dy, float *dx, void *dxb, float *dw, float *db, float *scratch, size_t scratch_floats);
+TWIST_API twist_status twist_rope_raw(twist_ctx *ctx, void *qkv, int32_t B, int32_t N, int32_t Hs, float sign, float *tab);
+TWIST_API twist_status twist_act_raw(twist_ctx *ctx, const void *gu, int32_t T, int32_t F, void *a, const void *da, void *dgu,
+                                     const int32_t *keep, int32_t unit);
+TWIST_API twist_status twist_ce_raw(twist_ctx *ctx, void *logits, int64_t ld, const int32_t *targets, int32_t T, float *rowloss, float *loss);
+TWIST_API twist_status twist_embed_raw(twist_ctx *ctx, const int32_t *tok, int32_t B, int32_t N, const void *tok_embed, const void *pos_embed,
+                                       float *x, const float *dx, float *d_tok, float *d_pos);
 
 /* Measurement aid for benchmarks (not part of the method): while enabled, every projection (GEMM) launch on
  * this ctx is bracketed by two HIP events on the ctx's stream.  twist_profile_gemm_read synchronises the
@@ -280,6 +319,16 @@ TWIST_API twist_status twist_profile_gemm_read(twist_ctx *ctx, int64_t *launches
  * kernel on the context's stream (needed when per-kernel durations are to be measured one at a time).
  * Default: enabled. */
 TWIST_API twist_status twist_set_overlap(twist_ctx *ctx, int32_t enable);
+
+/* Kernel selection for tests (not part of the method): by default every launcher picks its kernel from the shape.
+ *   gemm_tile        0 = by shape; 128 or 256 pins the tile of the matrix-core projection kernel and keeps the
+ *                    contraction in one piece (TWIST_EINVAL for other values);
+ *   plain_only       non-zero: projections and attention never use the matrix-core kernels (the plain fp32-arithmetic
+ *                    kernels that serve fp32 models and unaligned shapes run instead);
+ *   staged_attention non-zero: d_head = 128 attention runs the register-staged tiled kernels instead of the ones fed by
+ *                    loads straight into LDS.
+ * Results stay within the same tolerances under every choice; only speed changes. */
+TWIST_API twist_status twist_set_kernel_choice(twist_ctx *ctx, int32_t gemm_tile, int32_t plain_only, int32_t staged_attention);
 
 #ifdef __cplusplus
 }

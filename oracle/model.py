@@ -32,6 +32,13 @@ def _ident(tag, a):
     return a
 
 
+# Every tensor class the rounding hook is offered, i.e. every place where a bf16 model stores an activation or an
+# activation gradient between two kernels: normed inputs (h1, h2, hf), projections of them (qkv, also after the rotary
+# embedding; u: FFN pre-activations, gate included), attention output (o), FFN activation (a), logits; backward: the
+# loss gradient (dlogits), the residual-stream gradient handed to a module (dres) and every activation gradient (dact).
+HOOK_TAGS = ("h1", "qkv", "o", "h2", "u", "a", "hf", "logits", "dlogits", "dres", "dact")
+
+
 # ----------------------------------------------------------------------------- pieces
 def norm_fwd(x, w, b, kind, eps):
     if kind == "ln":
@@ -79,6 +86,49 @@ def act_bwd(u, kind):
 
 def sigmoid(x):
     return 1.0 / (1.0 + np.exp(-x))
+
+
+def swiglu_fwd(g, u):
+    """Gated FFN activation: silu(g) * u with silu(g) = g * sigmoid(g)."""
+    return g * sigmoid(g) * u
+
+
+def swiglu_bwd(g, u, da):
+    """(dg, du) of swiglu_fwd given the gradient da of its output."""
+    sg = sigmoid(g)
+    return da * u * (sg + g * sg * (1.0 - sg)), da * g * sg
+
+
+def cross_entropy(logits, tgt):
+    """Mean next-token cross-entropy over all leading positions of logits [..., V] with integer targets [...], and
+    its gradient with respect to the logits, (softmax - onehot) / #positions."""
+    m = logits.max(-1, keepdims=True)
+    lse = m[..., 0] + np.log(np.exp(logits - m).sum(-1))
+    picked = np.take_along_axis(logits, tgt[..., None], axis=-1)[..., 0]
+    loss = float((lse - picked).mean())
+    dlogits = np.exp(logits - lse[..., None])
+    np.put_along_axis(dlogits, tgt[..., None], np.take_along_axis(dlogits, tgt[..., None], -1) - 1.0, -1)
+    return loss, dlogits / lse.size
+
+
+def embed_fwd(tok, tok_embed, pos_embed=None):
+    """X_0 [B, N, d]: the token's embedding row plus (GPT) the learned embedding of its position."""
+    X = tok_embed[tok]
+    if pos_embed is not None:
+        X = X + pos_embed[None, :tok.shape[1], :]
+    return X
+
+
+def embed_bwd(tok, dX, d_tok_embed, n_pos=None):
+    """Adds dX [B, N, d] into the rows of d_tok_embed the batch used (in place); returns the gradient of the position
+    table [n_pos, d] (rows beyond N zero) when n_pos is given."""
+    B, N, _ = dX.shape
+    np.add.at(d_tok_embed, tok.reshape(-1), dX.reshape(B * N, -1))
+    if n_pos is None:
+        return None
+    dP = np.zeros((n_pos, dX.shape[-1]))
+    dP[:N] = dX.sum(0)
+    return dP
 
 
 def rope_tables(N, d_head, theta):
@@ -138,9 +188,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
     if lm:
         tok = np.asarray(inputs)
         B, N = tok.shape
-        X = G["tok_embed"][tok]
-        if "pos_embed" in G:
-            X = X + G["pos_embed"][None, :N, :]
+        X = embed_fwd(tok, G["tok_embed"], G.get("pos_embed"))
     else:
         X = np.asarray(inputs, dtype=np.float64)
         B, N, _ = X.shape
@@ -174,7 +222,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         if cfg.act == "swiglu":
             g = q("u", h2 @ lw["w_gate"].T)
             c["g"] = g
-            a = g * sigmoid(g) * u
+            a = swiglu_fwd(g, u)
         else:
             a = act_fwd(u, cfg.act)
         a = q("a", a)
@@ -188,11 +236,8 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         hf = q("hf", hf)
         W_out = G["tok_embed"] if cfg.tied_head else G["lm_head"]
         logits = q("logits", hf @ W_out.T)                                    # [B,N,V]
-        m = logits.max(-1, keepdims=True)
-        lse = m[..., 0] + np.log(np.exp(logits - m).sum(-1))
         tgt = np.asarray(targets)
-        picked = np.take_along_axis(logits, tgt[..., None], axis=-1)[..., 0]
-        loss = float((lse - picked).mean())
+        loss, dlogits = cross_entropy(logits, tgt)
     else:
         Y = np.asarray(targets, dtype=np.float64)
         loss = float(((X - Y) ** 2).mean())
@@ -202,9 +247,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
     # ------------------------------------------------------------------ backward
     grads = {"layers": [None] * len(P["layers"]), "globals": {}}
     if lm:
-        dlogits = np.exp(logits - lse[..., None])
-        np.put_along_axis(dlogits, tgt[..., None], np.take_along_axis(dlogits, tgt[..., None], -1) - 1.0, -1)
-        dlogits = q("dlogits", dlogits / (B * N))
+        dlogits = q("dlogits", dlogits)
         dW_out = dlogits.reshape(B * N, -1).T @ hf.reshape(B * N, -1)
         dhf = q("dact", dlogits @ W_out)
         dX, dw, db = norm_bwd(dhf, G["final_norm_w"], nf, cfg.norm)
@@ -233,10 +276,8 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
             g_["b_down"] = dy2f.sum(0)
         da = q("dact", dy2 @ lw["w_down"])
         if cfg.act == "swiglu":
-            g, u = c["g"], c["u"]
-            sg = sigmoid(g)
-            du = q("dact", da * g * sg)
-            dg = q("dact", da * u * (sg + g * sg * (1.0 - sg)))
+            dg, du = swiglu_bwd(c["g"], c["u"], da)
+            dg, du = q("dact", dg), q("dact", du)
             g_["w_gate"] = dg.reshape(T, -1).T @ c["h2"].reshape(T, -1)
             dh2 = dg @ lw["w_gate"]
         else:
@@ -275,11 +316,8 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         grads["layers"][li] = g_
 
     if lm:
-        dE = grads["globals"]["tok_embed"]
-        np.add.at(dE, tok.reshape(-1), dX.reshape(B * N, -1))
-        if "pos_embed" in G:
-            dP = np.zeros_like(G["pos_embed"])
-            dP[:N] = dX.sum(0)
+        dP = embed_bwd(tok, dX, grads["globals"]["tok_embed"], G["pos_embed"].shape[0] if "pos_embed" in G else None)
+        if dP is not None:
             grads["globals"]["pos_embed"] = dP
     else:
         grads["input"] = dX

@@ -6,7 +6,7 @@ N_full blocks, S subnets, N_sub blocks per subnet, common set C, blueprint A (S 
 Readings where the text is silent (all also listed in the design notes):
   * C' (never defined) is the complement of C, randomly permuted, since the section says the
     subnets are drawn uniformly at random while nothing else in that loop is random.
-  * A starts filled with a sentinel that does not count as "filled".
+  * A's unassigned slots do not count as "filled" (rows are kept as sets of assigned blocks here).
   * N_empty = 0 means "nothing to top up".
   * unique_choice draws uniformly without replacement from the ascending complement of the row.
   * deployment ("we relax our constraints"): no coverage pass; each row is C plus a uniform
@@ -15,7 +15,6 @@ Readings where the text is silent (all also listed in the design notes):
 from .rng import Stream
 
 KIND_HEAD, KIND_FFN = 0, 1
-EMPTY = -1
 
 
 class ConstraintError(ValueError):
@@ -32,26 +31,23 @@ def generate_blueprint(n_full, S, n_sub, common, stream, require_coverage=True):
     if require_coverage and n_full - c > S * (n_sub - c):
         raise ConstraintError("N_full - |C| <= S (N_sub - |C|) violated")
 
-    A = [[EMPTY] * n_sub for _ in range(S)]
-    # common blocks first
-    for s in range(S):
-        A[s][:c] = C
-    # deal every other block once, round-robin, so each block is trained by someone
+    # Each subnet's blueprint row is kept as a membership set: what matters about A[s, :] is which blocks it names
+    # (the row is returned in ascending order, so slot positions carry no information).
+    members = [set(C) for _ in range(S)]                     # every subnet holds the common blocks
     if require_coverage:
-        in_c = set(C)
-        c_prime = [b for b in range(n_full) if b not in in_c]
-        stream.shuffle(c_prime)
-        for i, b in enumerate(c_prime):
-            A[i % S][c + i // S] = b
-    # top each row up to N_sub
+        # coverage: the blocks outside C, in random order, are dealt to the subnets in turn, one block each per turn,
+        # so every block is trained by exactly one subnet before anything is drawn freely
+        rest = [b for b in range(n_full) if b not in members[0]]
+        stream.shuffle(rest)
+        for turn, b in enumerate(rest):
+            members[turn % S].add(b)
     for s in range(S):
-        filled = [b for b in A[s] if b != EMPTY]
-        n_empty = n_sub - len(filled)
-        if n_empty > 0:
-            have = set(filled)
-            pool = [b for b in range(n_full) if b not in have]
-            A[s][n_sub - n_empty:] = stream.unique_choice(pool, n_empty)
-    return [sorted(row) for row in A]
+        # top-up: whatever the subnet still lacks is drawn uniformly, without replacement, from the blocks it does not hold
+        lacking = n_sub - len(members[s])
+        if lacking > 0:
+            outside = [b for b in range(n_full) if b not in members[s]]
+            members[s].update(stream.unique_choice(outside, lacking))
+    return [sorted(m) for m in members]
 
 
 def inverse_and_count(A, n_full):

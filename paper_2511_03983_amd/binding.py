@@ -26,7 +26,7 @@ NORM = {"ln": 0, "rms": 1}
 KIND_HEAD, KIND_FFN = 0, 1
 SCALE_NONE, SCALE_SQRT_RATIO = 0, 1
 OPT_SGD, OPT_ADAMW = 0, 1
-PARAM, GRAD = 0, 1
+PARAM, GRAD, MASTER, ADAM_M, ADAM_V = 0, 1, 2, 3, 4
 STORE_PARAMS, STORE_GRADS, STORE_ADAMW = 0, 1, 2
 LAYER_TENSORS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "bq", "bk", "bv", "bo", "b_up", "b_down",
                  "norm1_w", "norm1_b", "norm2_w", "norm2_b")
@@ -75,6 +75,7 @@ _SIGS = {
     "twist_last_error": ([_vp], C.c_char_p),
     "twist_sample": ([_vp, C.POINTER(SampleDesc), C.POINTER(_vp)], _i32),
     "twist_plan_view": ([_vp, _i32, _i32, C.POINTER(_PI32), C.POINTER(_PI32), C.POINTER(_PI32), _PI32, _PI32, _i32], _i32),
+    "twist_plan_read_device": ([_vp, _i32, _i32, _PI32, _PI32, _PI32], _i32),
     "twist_plan_destroy": ([_vp], None),
     "twist_subnet_bytes": ([_vp, _vp, _i32, C.POINTER(_sz)], _i32),
     "twist_extract": ([_vp, _vp, C.POINTER(FullWeightsC), _i32, _vp, _sz, _i32, C.POINTER(_vp)], _i32),
@@ -95,7 +96,13 @@ _SIGS = {
     "twist_round_bytes": ([_vp, C.POINTER(RoundDesc), C.POINTER(_sz), C.POINTER(_sz), C.POINTER(_sz)], _i32),
     "twist_round": ([_vp, C.POINTER(RoundDesc), C.POINTER(FullWeightsC), _vp, _vp, _vp, _sz, _vp, _sz, _vp, _sz, _vp], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
-    "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp], _i32),
+    "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
+    "twist_norm_raw": ([_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz], _i32),
+    "twist_rope_raw": ([_vp, _vp, _i32, _i32, _i32, C.c_float, _vp], _i32),
+    "twist_act_raw": ([_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32], _i32),
+    "twist_ce_raw": ([_vp, _vp, C.c_int64, _vp, _i32, _vp, _vp], _i32),
+    "twist_embed_raw": ([_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
+    "twist_set_kernel_choice": ([_vp, _i32, _i32, _i32], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
     "twist_set_overlap": ([_vp, _i32], _i32),
     "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
@@ -104,6 +111,11 @@ for _name, (_args, _res) in _SIGS.items():
     _f = getattr(lib, _name)          # AttributeError here = the library lacks a declared entry point
     _f.argtypes, _f.restype = _args, _res
 EXPORTS = tuple(_SIGS)
+
+
+def _ptr(t):
+    """Device address of a tensor as a void pointer argument (None stays NULL)."""
+    return None if t is None else _vp(t.data_ptr())
 
 
 def _check(status, ctx=None):
@@ -248,8 +260,9 @@ class Context:
                                   _vp(out.data_ptr()), out.stride(0), int(out.dtype == torch.float32 and self.torch_dtype != torch.float32
                                                                           or out.dtype == torch.float32), alpha), self.h)
 
-    def twist_attention_raw(self, qkv: torch.Tensor, dout, B: int, N: int, Hs: int):
-        """Causal attention alone: returns (o, lse, dqkv or None) for qkv [B*N, 3*Hs*d_head] and dout [B*N, Hs*d_head] or None."""
+    def twist_attention_raw(self, qkv: torch.Tensor, dout, B: int, N: int, Hs: int, keep: torch.Tensor | None = None):
+        """Causal attention alone: returns (o, lse, dqkv or None) for qkv [B*N, 3*Hs*d_head] and dout [B*N, Hs*d_head] or None;
+        keep: int32 [Hs] head mask (entries < 0 are masked) or None."""
         T, HD = B * N, qkv.shape[1] // 3
         o = torch.empty((T, HD), dtype=qkv.dtype, device=qkv.device)
         o32 = torch.empty((T, HD), dtype=torch.float32, device=qkv.device)
@@ -258,8 +271,59 @@ class Context:
         dqkv = torch.empty_like(qkv) if dout is not None else None
         _check(lib.twist_attention_raw(self.h, _vp(qkv.data_ptr()), _vp(dout.data_ptr()) if dout is not None else None, B, N, Hs,
                                        _vp(o.data_ptr()), _vp(o32.data_ptr()), _vp(lse.data_ptr()), _vp(delta.data_ptr()),
-                                       _vp(dqkv.data_ptr()) if dqkv is not None else None), self.h)
+                                       _vp(dqkv.data_ptr()) if dqkv is not None else None, _ptr(keep)), self.h)
         return o, lse, dqkv
+
+    def twist_norm_raw(self, x: torch.Tensor, w: torch.Tensor, b, dy=None):
+        """y = f_ln(x) for x fp32 [T, d_model]; with dy also (dx fp32, dxb, dw, db or None).  Returns (y, stats, backward tuple or None)."""
+        T, D = x.shape
+        y = torch.empty((T, D), dtype=self.torch_dtype, device=x.device)
+        stats = torch.empty((T, 2), dtype=torch.float32, device=x.device)
+        if dy is None:
+            _check(lib.twist_norm_raw(self.h, _ptr(x), _ptr(w), _ptr(b), T, _ptr(y), _ptr(stats), None, None, None, None, None, None, 0), self.h)
+            return y, stats, None
+        dx = torch.empty_like(x)
+        dxb = torch.empty_like(y)
+        dw = torch.empty(D, dtype=torch.float32, device=x.device)
+        db = torch.empty(D, dtype=torch.float32, device=x.device) if b is not None else None
+        scratch = torch.empty(((T + 15) // 16) * 2 * D, dtype=torch.float32, device=x.device)
+        _check(lib.twist_norm_raw(self.h, _ptr(x), _ptr(w), _ptr(b), T, _ptr(y), _ptr(stats), _ptr(dy), _ptr(dx), _ptr(dxb), _ptr(dw), _ptr(db),
+                                  _ptr(scratch), scratch.numel()), self.h)
+        return y, stats, (dx, dxb, dw, db)
+
+    def twist_rope_raw(self, qkv: torch.Tensor, B: int, N: int, Hs: int, sign: float = 1.0) -> None:
+        """Rotary positions applied in place to the q and k heads of qkv [B*N, 3*Hs*d_head]."""
+        tab = torch.empty(N * self.desc.d_head, dtype=torch.float32, device=qkv.device)
+        _check(lib.twist_rope_raw(self.h, _ptr(qkv), B, N, Hs, sign, _ptr(tab)), self.h)
+
+    def twist_act_raw(self, gu: torch.Tensor, F: int, da=None, keep=None, unit: int = 1):
+        """(a, dgu or None): the FFN activation on gu [T, F] (or [T, 2F] gate | up) and its backward for da [T, F]."""
+        T = gu.shape[0]
+        a = torch.empty((T, F), dtype=gu.dtype, device=gu.device)
+        dgu = torch.empty_like(gu) if da is not None else None
+        _check(lib.twist_act_raw(self.h, _ptr(gu), T, F, _ptr(a), _ptr(da), _ptr(dgu), _ptr(keep), unit), self.h)
+        return a, dgu
+
+    def twist_ce_raw(self, logits: torch.Tensor, targets: torch.Tensor):
+        """Mean cross-entropy of logits [T, ld] (overwritten by its gradient); returns (loss tensor, rowloss)."""
+        T = logits.shape[0]
+        rowloss = torch.empty(max(T, 1024), dtype=torch.float32, device=logits.device)
+        loss = torch.zeros(1, dtype=torch.float32, device=logits.device)
+        _check(lib.twist_ce_raw(self.h, _ptr(logits), logits.stride(0), _ptr(targets), T, _ptr(rowloss), _ptr(loss)), self.h)
+        return loss, rowloss[:T]
+
+    def twist_embed_raw(self, tok: torch.Tensor, tok_embed: torch.Tensor, pos_embed=None, dx=None):
+        """x fp32 [B*N, d_model] = embedding rows (+ positions); with dx also (d_tok, d_pos or None)."""
+        B, N = tok.shape
+        D = tok_embed.shape[1]
+        x = torch.empty((B * N, D), dtype=torch.float32, device=tok.device)
+        d_tok = torch.zeros(tok_embed.shape, dtype=torch.float32, device=tok.device) if dx is not None else None
+        d_pos = torch.empty((N, D), dtype=torch.float32, device=tok.device) if (dx is not None and pos_embed is not None) else None
+        _check(lib.twist_embed_raw(self.h, _ptr(tok), B, N, _ptr(tok_embed), _ptr(pos_embed), _ptr(x), _ptr(dx), _ptr(d_tok), _ptr(d_pos)), self.h)
+        return x, d_tok, d_pos
+
+    def twist_set_kernel_choice(self, gemm_tile: int = 0, plain_only: bool = False, staged_attention: bool = False) -> None:
+        _check(lib.twist_set_kernel_choice(self.h, gemm_tile, int(plain_only), int(staged_attention)), self.h)
 
     def twist_set_overlap(self, enable: bool) -> None:
         _check(lib.twist_set_overlap(self.h, int(enable)), self.h)
@@ -286,6 +350,14 @@ class Plan:
         S, ns, nf = self.S, ns.value, nf.value
         as_t = lambda p, n: torch.tensor(p[:n], dtype=torch.int32)
         return as_t(idx, S * ns).view(S, ns), as_t(inv, S * nf).view(S, nf), as_t(cnt, nf)
+
+    def twist_plan_read_device(self, layer: int, kind: int):
+        """(idx [S, n_sub], inv [S, n_full], count [n_full]) as int32 torch tensors, copied back from the DEVICE tables."""
+        _, _, _, ns, nf = self.device_tables(layer, kind)
+        idx, inv, cnt = (C.c_int32 * (self.S * ns))(), (C.c_int32 * (self.S * nf))(), (C.c_int32 * nf)()
+        _check(lib.twist_plan_read_device(self.h, layer, kind, idx, inv, cnt), self.ctx.h)
+        as_t = lambda a: torch.tensor(list(a), dtype=torch.int32)
+        return as_t(idx).view(self.S, ns), as_t(inv).view(self.S, nf), as_t(cnt)
 
     def device_tables(self, layer: int, kind: int):
         """Raw device addresses of (idx, inv, count) and (n_sub, n_full)."""
@@ -333,7 +405,7 @@ class Subnet:
         t = names.index(tensor) if isinstance(tensor, str) else tensor
         dev, shape = _vp(), (C.c_int64 * 2)()
         _check(lib.twist_subnet_view(self.h, layer, t, what, C.byref(dev), shape), self.ctx.h)
-        dt = self.ctx.torch_dtype if what == PARAM else torch.float32
+        dt = self.ctx.torch_dtype if what == PARAM else torch.float32      # gradient, master weights and moments are fp32
         n = shape[0] * shape[1]
         off = dev.value - self.storage.data_ptr()
         v = self.storage[off: off + n * dt.itemsize].view(dt)

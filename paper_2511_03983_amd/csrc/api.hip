@@ -359,6 +359,17 @@ extern "C" twist_status twist_plan_view(const twist_plan *plan, int32_t layer, i
   return TWIST_OK;
 }
 
+extern "C" twist_status twist_plan_read_device(const twist_plan *plan, int32_t layer, int32_t kind, int32_t *idx, int32_t *inv, int32_t *count) {
+  if (!plan) TW_FAIL(nullptr, TWIST_EINVAL, "twist_plan_read_device: null plan");
+  if (layer < 0 || layer >= plan->ctx->d.n_layers || kind < 0 || kind > 1)
+    TW_FAIL(plan->ctx, TWIST_EINVAL, "twist_plan_read_device: layer %d / kind %d out of range", layer, kind);
+  const PlanEntry &pe = plan->at(layer, kind);
+  if (idx) TW_HIP(plan->ctx, hipMemcpy(idx, pe.d_idx, pe.idx.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+  if (inv) TW_HIP(plan->ctx, hipMemcpy(inv, pe.d_inv, pe.inv.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+  if (count) TW_HIP(plan->ctx, hipMemcpy(count, pe.d_count, pe.count.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+  return TWIST_OK;
+}
+
 extern "C" void twist_plan_destroy(twist_plan *plan) {
   if (!plan) return;
   if (plan->d_tables) (void)hipFree(plan->d_tables);
@@ -510,12 +521,11 @@ twist_status bind_subnet(twist_ctx *ctx, const twist_plan *plan, int32_t s, void
   return TWIST_OK;
 }
 
-// after the weights are in place: fp32 master copy, zeroed gradient and moment regions
+// After the weights are in place: the fp32 master copy.  The gradient region is not cleared (twist_subnet_fwd_bwd
+// overwrites every gradient) and neither are the AdamW moments: the first step of a subnet takes them as zero without
+// reading them (twist_adamw with step = 1), which saves three sweeps over the subnet per extract.
 twist_status finish_subnet(twist_ctx *ctx, const twist_plan *plan, twist_subnet *sub) {
-  const size_t fb = region_bytes(plan, 4);
   if (sub->master) TW_TRY(twist_launch_to_f32(ctx, sub->params, sub->master, plan->layout.n_total));
-  if (sub->grads) TW_TRY(twist_launch_zero(ctx, sub->grads, fb));
-  if (sub->adam_m) TW_TRY(twist_launch_zero(ctx, sub->adam_m, 2 * fb));
   return TWIST_OK;
 }
 
@@ -592,6 +602,14 @@ extern "C" twist_status twist_subnet_view(const twist_subnet *sub, int32_t layer
   else if (what == TWIST_GRAD) {
     if (!sub->grads) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_view: subnet was extracted without gradient storage");
     *dev = sub->grads + slot.off;
+  } else if (what == TWIST_MASTER) {
+    // fp32 models keep no separate master copy: the parameters are the fp32 weights the optimizer updates
+    if (ctx->d.dtype == TWIST_BF16 && !sub->master) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_view: subnet was extracted without master weights");
+    *dev = ctx->d.dtype == TWIST_BF16 ? static_cast<void *>(sub->master + slot.off) : static_cast<void *>(sub->params + slot.off * 4);
+  } else if (what == TWIST_ADAM_M || what == TWIST_ADAM_V) {
+    if (!sub->adam_m) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_view: subnet was extracted without AdamW moments");
+    if (sub->step_count == 0) TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_view: the AdamW moments hold nothing before the first step");
+    *dev = (what == TWIST_ADAM_M ? sub->adam_m : sub->adam_v) + slot.off;
   } else TW_FAIL(ctx, TWIST_EINVAL, "twist_subnet_view: unknown selector %d", what);
   shape[0] = slot.rows;
   shape[1] = slot.cols;
@@ -757,17 +775,37 @@ int store_of(const twist_opt_desc &o) { return o.kind == TWIST_OPT_ADAMW ? TWIST
 extern "C" twist_status twist_round_bytes(twist_ctx *ctx, const twist_round_desc *rd, size_t *subnet_bytes, size_t *workspace_bytes,
                                           size_t *image_bytes) {
   if (!ctx || !rd || !subnet_bytes || !workspace_bytes || !image_bytes) TW_FAIL(ctx, TWIST_EINVAL, "twist_round_bytes: null argument");
-  twist_plan *plan = nullptr;
-  TW_TRY(twist_sample(ctx, &rd->sample, &plan));  // sizes depend on the widths only, not on the draw
+  // Sizes depend on the widths only, not on the draw: a plan without tables (host object only, nothing sampled,
+  // nothing allocated on the device) carries the subnet layout the two size queries read.
+  const twist_sample_desc &sd = rd->sample;
+  const twist_model_desc &d = ctx->d;
+  if (sd.S < 1 || sd.S > TWIST_MAX_S) TW_FAIL(ctx, TWIST_EINVAL, "twist_round_bytes: S=%d outside [1, %d]", sd.S, TWIST_MAX_S);
+  twist_plan widths;
+  widths.ctx = ctx;
+  widths.S = sd.S;
+  widths.e.resize((size_t)d.n_layers * 2);
+  bool any_drawn = false;
+  for (int l = 0; l < d.n_layers; ++l) any_drawn = any_drawn || !(sd.layer_shared && sd.layer_shared[l]);
+  for (int kind = 0; any_drawn && kind < 2; ++kind) {
+    const bool head = kind == TWIST_KIND_HEAD;
+    TW_TRY(check_blueprint_args(ctx, head ? d.n_heads : ctx->n_ffn_units(), sd.S, head ? sd.heads_sub : sd.ffn_units_sub,
+                                head ? sd.common_heads : sd.common_ffn, head ? sd.n_common_heads : sd.n_common_ffn, sd.require_coverage != 0));
+  }
+  for (int l = 0; l < d.n_layers; ++l)
+    for (int kind = 0; kind < 2; ++kind) {
+      PlanEntry &pe = widths.e[(size_t)l * 2 + kind];
+      pe.n_full = kind == TWIST_KIND_HEAD ? d.n_heads : ctx->n_ffn_units();
+      pe.n_sub = (sd.layer_shared && sd.layer_shared[l]) ? pe.n_full : (kind == TWIST_KIND_HEAD ? sd.heads_sub : sd.ffn_units_sub);
+    }
+  build_layout(ctx, &widths);
   size_t sb = 0, wb = 0, ib = 0;
-  twist_status st = twist_subnet_bytes(ctx, plan, store_of(rd->opt), &sb);
+  twist_status st = twist_subnet_bytes(ctx, &widths, store_of(rd->opt), &sb);
   if (st == TWIST_OK) {
     twist_subnet probe;
-    probe.ctx = ctx; probe.plan = plan;
+    probe.ctx = ctx; probe.plan = &widths;
     st = twist_train_workspace_bytes(ctx, &probe, rd->B, rd->N, &wb);
   }
   if (st == TWIST_OK) st = twist_aggregate_image_bytes(ctx, &ib);
-  twist_plan_destroy(plan);
   if (st != TWIST_OK) return st;
   *subnet_bytes = sb; *workspace_bytes = wb; *image_bytes = ib;
   return TWIST_OK;

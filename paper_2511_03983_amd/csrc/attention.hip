@@ -42,7 +42,7 @@ __device__ __forceinline__ RowId row_id(int B, int N, int Hs) {
 }
 
 template <int BF>
-__global__ __launch_bounds__(256) void attn_fwd_plain(const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh, float scale) {
+__global__ __launch_bounds__(256) void attn_fwd_plain(const void *qkv, void *o, float *lse, int B, int N, int Hs, int dh, float scale, const int32_t *keep) {
   const RowId r = row_id(B, N, Hs);
   if (!r.ok) return;
   const int lane = threadIdx.x & 63;
@@ -52,6 +52,13 @@ __global__ __launch_bounds__(256) void attn_fwd_plain(const void *qkv, void *o, 
 #pragma unroll
   for (int t = 0; t < kE; ++t) { int e = lane + 64 * t; q[t] = e < dh ? El<BF>::ld(qkv, qoff + e) : 0.f; acc[t] = 0.f; }
   float m = -INFINITY, l = 0.f;
+  const int64_t ooff = ((int64_t)r.b * N + r.i) * HD + (int64_t)r.h * dh;
+  if (keep && keep[r.h] < 0) {  // masked head (Masked TwIST, Section 4.1): its output is zero
+#pragma unroll
+    for (int t = 0; t < kE; ++t) { int e = lane + 64 * t; if (e < dh) El<BF>::st(o, ooff + e, 0.f); }
+    if (lane == 0) lse[((int64_t)r.b * Hs + r.h) * N + r.i] = 0.f;
+    return;
+  }
   for (int j = 0; j <= r.i; ++j) {
     const int64_t koff = ((int64_t)r.b * N + j) * ld + HD + (int64_t)r.h * dh;
     float s = 0.f;
@@ -65,7 +72,6 @@ __global__ __launch_bounds__(256) void attn_fwd_plain(const void *qkv, void *o, 
     for (int t = 0; t < kE; ++t) { int e = lane + 64 * t; if (e < dh) acc[t] = acc[t] * c + p * El<BF>::ld(qkv, koff + HD + e); }
     m = mn;
   }
-  const int64_t ooff = ((int64_t)r.b * N + r.i) * HD + (int64_t)r.h * dh;
 #pragma unroll
   for (int t = 0; t < kE; ++t) { int e = lane + 64 * t; if (e < dh) El<BF>::st(o, ooff + e, acc[t] / l); }
   if (lane == 0) lse[((int64_t)r.b * Hs + r.h) * N + r.i] = m + logf(l);
@@ -76,7 +82,7 @@ __global__ __launch_bounds__(256) void attn_fwd_plain(const void *qkv, void *o, 
 // here from the same p and dp the gradient uses (a first pass over the keys) instead of from the stored o.
 template <int BF>
 __global__ __launch_bounds__(256) void attn_bwd_dq_plain(const void *qkv, const void *dout, const float *lse, float *delta, void *dqkv, int B,
-                                                         int N, int Hs, int dh, float scale) {
+                                                         int N, int Hs, int dh, float scale, const int32_t *keep) {
   const RowId r = row_id(B, N, Hs);
   if (!r.ok) return;
   const int lane = threadIdx.x & 63;
@@ -93,7 +99,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_plain(const void *qkv, const 
     acc[t] = 0.f;
   }
   float Dl = 0.f;
-  for (int j = 0; j <= r.i; ++j) {
+  const int n_keys = (keep && keep[r.h] < 0) ? 0 : r.i + 1;  // masked head: zero gradient, no key is visited
+  for (int j = 0; j < n_keys; ++j) {
     const int64_t koff = ((int64_t)r.b * N + j) * ld + HD + (int64_t)r.h * dh;
     float s = 0.f, dp = 0.f;
 #pragma unroll
@@ -104,7 +111,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_plain(const void *qkv, const 
     Dl += __expf(wave_sum(s) * scale - L) * wave_sum(dp);
   }
   if (lane == 0) delta[((int64_t)r.b * Hs + r.h) * N + r.i] = Dl;
-  for (int j = 0; j <= r.i; ++j) {
+  for (int j = 0; j < n_keys; ++j) {
     const int64_t koff = ((int64_t)r.b * N + j) * ld + HD + (int64_t)r.h * dh;
     float s = 0.f, dp = 0.f;
 #pragma unroll
@@ -124,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_plain(const void *qkv, const 
 
 template <int BF>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_plain(const void *qkv, const void *dout, const float *lse, const float *delta, void *dqkv, int B,
-                                                          int N, int Hs, int dh, float scale) {
+                                                          int N, int Hs, int dh, float scale, const int32_t *keep) {
   const RowId r = row_id(B, N, Hs);  // r.i is the key/value row j
   if (!r.ok) return;
   const int lane = threadIdx.x & 63;
@@ -138,7 +145,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_plain(const void *qkv, const
     v[t] = e < dh ? El<BF>::ld(qkv, koff + HD + e) : 0.f;
     dk[t] = dv[t] = 0.f;
   }
-  for (int i = r.i; i < N; ++i) {
+  const int n_q = (keep && keep[r.h] < 0) ? 0 : N;  // masked head: zero gradients
+  for (int i = r.i; i < n_q; ++i) {
     const int64_t qoff = ((int64_t)r.b * N + i) * ld + (int64_t)r.h * dh;
     const int64_t doff = ((int64_t)r.b * N + i) * HD + (int64_t)r.h * dh;
     float qv[kE], gv[kE];
@@ -168,55 +176,57 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_plain(const void *qkv, const
 
 }  // namespace
 
-twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, bool *done);
+twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, const int32_t *keep,
+                                      bool *done);
 twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                      void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab, bool *done, bool *rope_done);
+                                      void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab, const int32_t *keep, bool *done, bool *rope_done);
 
-twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh) {
+twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh,
+                                 const int32_t *keep) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
   const float scale = 1.0f / sqrtf((float)dh);
   if (bf16) {
     bool done = false;
-    TW_TRY(twist_attention_fwd_mfma(ctx, qkv, o, o32, lse, B, N, Hs, dh, &done));
+    TW_TRY(twist_attention_fwd_mfma(ctx, qkv, o, o32, lse, B, N, Hs, dh, keep, &done));
     if (done) return TWIST_OK;
   }
   dim3 grid((unsigned)(((int64_t)B * Hs * N + 3) / 4)), block(256);
-  if (bf16) hipLaunchKernelGGL(attn_fwd_plain<1>, grid, block, 0, ctx->stream, qkv, o, lse, B, N, Hs, dh, scale);
-  else hipLaunchKernelGGL(attn_fwd_plain<0>, grid, block, 0, ctx->stream, qkv, o, lse, B, N, Hs, dh, scale);
+  if (bf16) hipLaunchKernelGGL(attn_fwd_plain<1>, grid, block, 0, ctx->stream, qkv, o, lse, B, N, Hs, dh, scale, keep);
+  else hipLaunchKernelGGL(attn_fwd_plain<0>, grid, block, 0, ctx->stream, qkv, o, lse, B, N, Hs, dh, scale, keep);
   TW_HIP(ctx, hipGetLastError());
   return TWIST_OK;
 }
 
 twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab) {
+                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab, const int32_t *keep) {
   if (dh > 64 * kE) TW_FAIL(ctx, TWIST_ESHAPE, "attention: d_head=%d above %d is not supported", dh, 64 * kE);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)(((int64_t)B * Hs * N + 3) / 4)), block(256);
   if (bf16) {
     bool done = false, rope_done = false;
-    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, dh, rope_tab, &done, &rope_done));
+    TW_TRY(twist_attention_bwd_mfma(ctx, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, dh, rope_tab, keep, &done, &rope_done));
     if (done) return (rope_tab && !rope_done) ? twist_rope_apply(ctx, bf16, dqkv, rope_tab, B, N, Hs, dh, -1.f) : TWIST_OK;
   }
   if (bf16) {
-    hipLaunchKernelGGL(attn_bwd_dq_plain<1>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
-    hipLaunchKernelGGL(attn_bwd_dkv_plain<1>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
+    hipLaunchKernelGGL(attn_bwd_dq_plain<1>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale, keep);
+    hipLaunchKernelGGL(attn_bwd_dkv_plain<1>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale, keep);
   } else {
-    hipLaunchKernelGGL(attn_bwd_dq_plain<0>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
-    hipLaunchKernelGGL(attn_bwd_dkv_plain<0>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale);
+    hipLaunchKernelGGL(attn_bwd_dq_plain<0>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale, keep);
+    hipLaunchKernelGGL(attn_bwd_dkv_plain<0>, grid, block, 0, ctx->stream, qkv, dout, lse, delta, dqkv, B, N, Hs, dh, scale, keep);
   }
   TW_HIP(ctx, hipGetLastError());
   return rope_tab ? twist_rope_apply(ctx, bf16, dqkv, rope_tab, B, N, Hs, dh, -1.f) : TWIST_OK;
 }
 
 extern "C" twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs, void *o, float *o32,
-                                            float *lse, float *delta, void *dqkv) {
+                                            float *lse, float *delta, void *dqkv, const int32_t *keep) {
   if (!ctx || !qkv || !o || !o32 || !lse) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: null argument");
   if (B < 1 || N < 1 || Hs < 1) TW_FAIL(ctx, TWIST_ESHAPE, "twist_attention_raw: empty shape");
   const int bf = ctx->d.dtype == TWIST_BF16;
-  TW_TRY(twist_attention_fwd(ctx, bf, qkv, o, o32, lse, B, N, Hs, ctx->d.d_head));
+  TW_TRY(twist_attention_fwd(ctx, bf, qkv, o, o32, lse, B, N, Hs, ctx->d.d_head, keep));
   if (dout) {
     if (!delta || !dqkv) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: backward needs delta and dqkv");
-    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head, nullptr));
+    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head, nullptr, keep));
   }
   return TWIST_OK;
 }

@@ -17,6 +17,10 @@
 // convex combination of the value rows; the dQ kernel forms delta from that fp32 output in its prologue.  With
 // both in place a component common to all value rows (a large value bias) cancels exactly in p (dp - delta),
 // which it does not when delta is taken from the bf16-rounded output.
+//
+// MASKED HEADS (Masked TwIST, Section 4.1: the full-width model with y = M * f(x)): every kernel takes an optional table
+// `keep` with one entry per head; a head with keep[h] < 0 is masked, its output and its input gradients are written
+// as zeros and none of its keys are visited, so the masked pass needs no extra kernels.
 #include <type_traits>
 
 #include "nn.h"
@@ -90,7 +94,7 @@ __device__ __forceinline__ int snake_rank(int b, int nwg) {
 // ------------------------------------------------------------------------------------------- forward
 // grid: (N/128) * B * Hs workgroups of 4 waves; wave w owns query rows [qb*128 + 32w, +32)
 template <int DH>
-__global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
+__global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale, const int32_t *keep) {
   constexpr int KS = DH / 16, MT = DH / 32, LDK = DH + 8, LDV = DH + 16;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LDK];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LDV];
@@ -115,7 +119,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int n_tiles = (qb + 1) * 2;
+  const bool masked = keep && keep[h] < 0;  // a masked head (see MASKED HEADS above): no key is visited, zeros are written
+  const int n_tiles = masked ? 0 : (qb + 1) * 2;
   for (int kt = 0; kt < n_tiles; ++kt) {
     __syncthreads();
     load_tile<64, DH>(Ks, LDK, kp + (int64_t)kt * 64 * ld, ld);
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
       }
   }
   l += __shfl_xor(l, 32, 64);
-  const float inv = 1.f / l;
+  const float inv = masked ? 0.f : 1.f / l;
   uint16_t *op = o + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
         *reinterpret_cast<f32x4 *>(o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH + i * 32 + 8 * j + 4 * g) = w4;
       }
     }
-  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
+  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = masked ? 0.f : (m + log2f(l)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------- backward: dQ (and delta)
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const uint16_t *qkv, uin
 // dS^T = p (dp - delta) scale and dQ^T[dh][q] += K^T[dh][kv] dS^T[kv][q].
 template <int DH>
 __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
-                                                           uint16_t *dqkv, int N, int Hs, float scale) {
+                                                           uint16_t *dqkv, int N, int Hs, float scale, const int32_t *keep) {
   constexpr int KS = DH / 16, MT = DH / 32, LD = DH + 16;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * LD];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[64 * LD];
@@ -243,7 +248,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, 
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  const int n_tiles = (qb + 1) * 2;
+  const int n_tiles = (keep && keep[h] < 0) ? 0 : (qb + 1) * 2;  // masked head: the gradient is zero
   for (int kt = 0; kt < n_tiles; ++kt) {
     __syncthreads();
     load_tile<64, DH>(Ks, LD, kp + (int64_t)kt * 64 * ld, ld);
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const uint16_t *qkv, 
 // dV^T[dh][kv] += dO^T[dh][q] P[q][kv]  and  dK^T[dh][kv] += Q^T[dh][q] dS[q][kv].
 template <int DH>
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
-                                                            uint16_t *dqkv, int N, int Hs, float scale) {
+                                                            uint16_t *dqkv, int N, int Hs, float scale, const int32_t *keep) {
   constexpr int KS = DH / 16, MT = DH / 32, LD = DH + 16;
   __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * LD];
   __shared__ __attribute__((aligned(16))) uint16_t Gs[64 * LD];
@@ -327,7 +332,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const uint16_t *qkv,
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
-  for (int qt = kb * 2; qt < N / 64; ++qt) {
+  const int n_q = (keep && keep[h] < 0) ? 0 : N / 64;  // masked head: the gradients are zero
+  for (int qt = kb * 2; qt < n_q; ++qt) {
     __syncthreads();
     load_tile<64, DH>(Qs, LD, qp + (int64_t)qt * 64 * ld, ld);
     load_tile<64, DH>(Gs, LD, gp + (int64_t)qt * 64 * HD, HD);
@@ -474,7 +480,7 @@ struct TileLoader {
 #define DL_WAIT_VM0 __builtin_amdgcn_s_waitcnt(0x0f70)
 
 // two waves per SIMD (two workgroups per CU) is what lets one workgroup's softmax overlap the other's matrix work
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_fwd_dl_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_fwd_dl_kernel(const uint16_t *qkv, uint16_t *o, float *o32, float *lse, int N, int Hs, float scale, const int32_t *keep) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
   const int nqb = N / 128, nbh = gridDim.x / nqb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -504,9 +510,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int n_tiles = (qb + 1) * 2;
-  lk.issue(rs, smem, 0, wave);
-  lv.issue(rs, smem + TILE_B, 0, wave);
+  const bool masked = keep && keep[h] < 0;  // a masked head: no key is visited (and nothing is loaded), zeros are written
+  const int n_tiles = masked ? 0 : (qb + 1) * 2;
+  if (!masked) {
+    lk.issue(rs, smem, 0, wave);
+    lv.issue(rs, smem + TILE_B, 0, wave);
+  }
   auto step = [&](int kt, auto stage_c) {
     constexpr int ST = decltype(stage_c)::value;
     DL_WAIT_VM0;                    // this wave's pieces of tile kt have landed
@@ -581,7 +590,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     step(kt + 1, std::integral_constant<int, 1>());  // n_tiles is even
   }
   l += __shfl_xor(l, 32, 64);
-  const float inv = 1.f / l;
+  const float inv = masked ? 0.f : 1.f / l;
   uint16_t *op = o + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -594,7 +603,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         *reinterpret_cast<f32x4 *>(o32 + ((int64_t)b * N + q) * HD + (int64_t)h * DH + i * 32 + 8 * j + 4 * g) = w4;
       }
     }
-  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = (m + log2f(l)) * kLn2;
+  if (g == 0) lse[((int64_t)b * Hs + h) * N + q] = masked ? 0.f : (m + log2f(l)) * kLn2;
 }
 
 // Backward of the rotary embedding on a lane's 64 gradient values of one row (acc[i][4 j + e] is head-dim column
@@ -619,7 +628,7 @@ __device__ __forceinline__ void rope_grad(f32x16 (&acc)[MT], const float *tab, i
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void flash_bwd_dq_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *o32, const float *lse, float *delta,
-                                                              uint16_t *dqkv, int N, int Hs, float scale, const float *rope) {
+                                                              uint16_t *dqkv, int N, int Hs, float scale, const float *rope, const int32_t *keep) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
   const int nqb = N / 128, nbh = gridDim.x / nqb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -639,9 +648,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
   lv.init(ld, (uint32_t)((2 * HD + h * DH) * 2), wave, lane);
   ReadOffsets ro;
   ro.init(lane);
-  const int n_tiles = (qb + 1) * 2;
-  lk.issue(rs, smem, 0, wave);
-  lv.issue(rs, smem + TILE_B, 0, wave);
+  const bool masked = keep && keep[h] < 0;  // masked head: the gradient is zero, nothing is loaded
+  const int n_tiles = masked ? 0 : (qb + 1) * 2;
+  if (!masked) {
+    lk.issue(rs, smem, 0, wave);
+    lv.issue(rs, smem + TILE_B, 0, wave);
+  }
 
   bf16x8 qf[KS], gf[KS];
   const uint16_t *gp = dout + ((int64_t)b * N + q) * HD + (int64_t)h * DH;
@@ -717,7 +729,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 }
 
 __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
-                                                               uint16_t *dqkv, int N, int Hs, float scale, const float *rope) {
+                                                               uint16_t *dqkv, int N, int Hs, float scale, const float *rope, const int32_t *keep) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 2 * 512];  // + per stage: 64 log-sum-exps, 64 deltas
   const int nkb = N / 128, nbh = gridDim.x / nkb;
   const int rank = snake_rank(blockIdx.x, gridDim.x);
@@ -739,7 +751,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
   lg.init(HD, (uint32_t)(h * DH * 2), wave, lane);
   ReadOffsets ro;
   ro.init(lane);
-  const int qt0 = kb * 2, n_q = N / 64;
+  const bool masked = keep && keep[h] < 0;  // masked head: the gradients are zero, nothing is loaded
+  const int qt0 = kb * 2, n_q = masked ? qt0 : N / 64;
   auto issue = [&](int qt, int st) {
     lq.issue(rq, smem + st * STAGE_B, (uint32_t)qt * qstep, wave);
     lg.issue(rg, smem + st * STAGE_B + TILE_B, (uint32_t)qt * gstep, wave);
@@ -747,7 +760,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
     if (wave == 0) dma<4>(rl, smem + 2 * STAGE_B + st * 512, (uint32_t)((qt * 64 + lane) * 4));
     if (wave == 1) dma<4>(rd, smem + 2 * STAGE_B + st * 512 + 256, (uint32_t)((qt * 64 + lane) * 4));
   };
-  issue(qt0, 0);
+  if (!masked) issue(qt0, 0);
 
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
@@ -852,10 +865,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *q
 }  // namespace dl
 
 // the pipelined kernels address a whole batch element through one 32-bit buffer range
-bool dl_ok(int B, int N, int Hs, int dh) {
-  static const bool off = getenv("TWIST_FLASH_NO_DL") != nullptr;
-  (void)B;
-  return !off && (int64_t)N * 3 * Hs * dh * 2 < (1ll << 31);
+bool dl_ok(const twist_ctx *ctx, int N, int Hs, int dh) {
+  return !ctx->staged_attention && (int64_t)N * 3 * Hs * dh * 2 < (1ll << 31);
 }
 
 bool shape_ok(const void *a, const void *b, int N, int Hs, int dh) {
@@ -865,24 +876,25 @@ bool shape_ok(const void *a, const void *b, int N, int Hs, int dh) {
 
 }  // namespace
 
-twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, bool *done) {
-  static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
+twist_status twist_attention_fwd_mfma(twist_ctx *ctx, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh, const int32_t *keep,
+                                      bool *done) {
+  const bool off = ctx->plain_only;
   *done = false;
   if (off || !shape_ok(qkv, o, N, Hs, dh)) return TWIST_OK;
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv);
-  if (dh == 128 && dl_ok(B, N, Hs, dh)) hipLaunchKernelGGL(dl::flash_fwd_dl_kernel, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
-  else if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
-  else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale);
+  if (dh == 128 && dl_ok(ctx, N, Hs, dh)) hipLaunchKernelGGL(dl::flash_fwd_dl_kernel, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale, keep);
+  else if (dh == 128) hipLaunchKernelGGL(flash_fwd_kernel<128>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale, keep);
+  else hipLaunchKernelGGL(flash_fwd_kernel<64>, grid, block, 0, ctx->stream, x, static_cast<uint16_t *>(o), o32, lse, N, Hs, scale, keep);
   TW_HIP(ctx, hipGetLastError());
   *done = true;
   return TWIST_OK;
 }
 
 twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta, void *dqkv,
-                                      int B, int N, int Hs, int dh, const float *rope_tab, bool *done, bool *rope_done) {
-  static const bool off = getenv("TWIST_NO_MFMA") != nullptr;
+                                      int B, int N, int Hs, int dh, const float *rope_tab, const int32_t *keep, bool *done, bool *rope_done) {
+  const bool off = ctx->plain_only;
   *done = false;
   *rope_done = false;
   if (off || !o32 || !shape_ok(qkv, dout, N, Hs, dh) || (reinterpret_cast<uintptr_t>(dqkv) % 16) || (reinterpret_cast<uintptr_t>(o32) % 16)) return TWIST_OK;
@@ -890,17 +902,17 @@ twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const flo
   dim3 grid((unsigned)((int64_t)(N / 128) * B * Hs)), block(256);
   const uint16_t *x = static_cast<const uint16_t *>(qkv), *gout = static_cast<const uint16_t *>(dout);
   uint16_t *dx = static_cast<uint16_t *>(dqkv);
-  if (dh == 128 && dl_ok(B, N, Hs, dh)) {
+  if (dh == 128 && dl_ok(ctx, N, Hs, dh)) {
     const float *rt = rope_tab && (reinterpret_cast<uintptr_t>(rope_tab) % 16) == 0 ? rope_tab : nullptr;
-    hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, rt);
-    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, rt);
+    hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, rt, keep);
+    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, rt, keep);
     *rope_done = rt != nullptr;
   } else if (dh == 128) {
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, keep);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<128>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, keep);
   } else {
-    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale);
-    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale);
+    hipLaunchKernelGGL(flash_bwd_dq_kernel<64>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, keep);
+    hipLaunchKernelGGL(flash_bwd_dkv_kernel<64>, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, keep);
   }
   TW_HIP(ctx, hipGetLastError());
   *done = true;

@@ -543,11 +543,10 @@ int choose_ksplit(int M, int N, int K, int *kchunk) {
 }
 
 template <int AKM, int BKM>
-void launch_mfma(hipStream_t st, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
+void launch_mfma(hipStream_t st, int force_tile, int M, int N, int K, const uint16_t *a, int64_t lda, const uint16_t *b, int64_t ldb, const Ep &ep) {
   // the 256x256 ping-pong kernel (one persistent workgroup per CU) from 64 tiles up, else 128x128 tiles (4 waves of 64x64)
   const int big = ((M + 255) / 256) * ((N + 255) / 256);
-  const char *force = getenv("TWIST_GEMM_TILE");  // test knob: "256" or "128" pins the tile size
-  const bool use_big = force ? atoi(force) == 256 : big >= 64;
+  const bool use_big = force_tile ? force_tile == 256 : big >= 64;
   if (use_big) {
     const int tm = (M + 255) / 256, tn = (N + 255) / 256;
     hipLaunchKernelGGL((pp::gemm_pp_kernel<AKM, BKM, false>), dim3(std::min(tm * tn, 256)), dim3(512), 0, st, M, N, K, a, lda, b, ldb, ep, tm, tn, 1, K);
@@ -581,7 +580,7 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   } stop_recorder{stream, ev_stop};
   Ep ep{e.alpha, e.bias, e.residual, e.out, e.out_f32, ldc, 0};
   ep.vec_ok = ldc % 4 == 0 && aligned16(e.out) && (!e.residual || aligned16(e.residual));
-  static const bool no_mfma = getenv("TWIST_NO_MFMA") != nullptr;
+  const bool no_mfma = ctx->plain_only;
   // 16-byte chunks along k must not straddle the end of an operand row.  For y = x W with a ragged K the
   // caller pads x's rows (lda >= K rounded up to 8) with zeros; W's rows beyond K are never touched.
   const bool k_ok = lay == GEMM_TN || K % 8 == 0 || (lay == GEMM_NN && lda >= (K + 7) / 8 * 8);
@@ -592,7 +591,7 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
   if (vec_ok) {
     const uint16_t *a = static_cast<const uint16_t *>(A), *b = static_cast<const uint16_t *>(B);
     int kchunk = K;
-    const int ks = (e.splitk_ws && !e.bias && !e.residual && !getenv("TWIST_GEMM_TILE")) ? choose_ksplit(M, N, K, &kchunk) : 1;
+    const int ks = (e.splitk_ws && !e.bias && !e.residual && !ctx->gemm_tile) ? choose_ksplit(M, N, K, &kchunk) : 1;
     if (ks > 1 && (size_t)ks * M * N <= e.splitk_floats && aligned16(e.splitk_ws)) {
       const int tm = (M + 255) / 256, tn = (N + 255) / 256;
       Ep part{1.f, nullptr, nullptr, e.splitk_ws, 1, N, N % 4 == 0};
@@ -609,9 +608,9 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
       return TWIST_OK;
     }
     switch (lay) {
-      case GEMM_NT: launch_mfma<1, 1>(stream, M, N, K, a, lda, b, ldb, ep); break;
-      case GEMM_NN: launch_mfma<1, 0>(stream, M, N, K, a, lda, b, ldb, ep); break;
-      case GEMM_TN: launch_mfma<0, 0>(stream, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_NT: launch_mfma<1, 1>(stream, ctx->gemm_tile, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_NN: launch_mfma<1, 0>(stream, ctx->gemm_tile, M, N, K, a, lda, b, ldb, ep); break;
+      case GEMM_TN: launch_mfma<0, 0>(stream, ctx->gemm_tile, M, N, K, a, lda, b, ldb, ep); break;
     }
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
@@ -645,6 +644,15 @@ extern "C" twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M
 extern "C" twist_status twist_set_overlap(twist_ctx *ctx, int32_t enable) {
   if (!ctx) TW_FAIL(nullptr, TWIST_EINVAL, "twist_set_overlap: null ctx");
   ctx->overlap = enable != 0;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_set_kernel_choice(twist_ctx *ctx, int32_t gemm_tile, int32_t plain_only, int32_t staged_attention) {
+  if (!ctx) TW_FAIL(nullptr, TWIST_EINVAL, "twist_set_kernel_choice: null ctx");
+  if (gemm_tile != 0 && gemm_tile != 128 && gemm_tile != 256) TW_FAIL(ctx, TWIST_EINVAL, "twist_set_kernel_choice: gemm_tile must be 0, 128 or 256");
+  ctx->gemm_tile = gemm_tile;
+  ctx->plain_only = plain_only != 0;
+  ctx->staged_attention = staged_attention != 0;
   return TWIST_OK;
 }
 

@@ -464,6 +464,9 @@ __device__ __forceinline__ void pull_elem_staged(const MoveLaunch &ml, const Mov
   constexpr int VN = StageShape<ES>::VN, SEGV = StageShape<ES>::SEGV, SEG = SEGV * VN;
   constexpr int DUMMY = kStageRows * kChunk * SEG;  // first element of the dummy block
   static_assert(kStageRows == kThreads / 64, "one staged row per wave");
+  // largest LDS element index read: a span holds at most 512 elements behind a misalignment of at most VN - 1, so an owner's
+  // index stays below its own SEG-element slot; a non-owner reads DUMMY + (0 .. VN - 1), inside the dummy block's 2 VN elements
+  static_assert(SEG >= 512 + VN - 1 + 1 && StageShape<ES>::VECS * VN >= DUMMY + 2 * VN, "staged spans and dummy block fit the LDS array");
   typedef const E __attribute__((address_space(3))) *lds_elems;
   typedef const u32x4 __attribute__((address_space(1))) *global_vecs;  // plain global loads: they leave the LDS counter alone
   const lds_elems stage_e = (lds_elems)stage;
@@ -545,10 +548,14 @@ __device__ __forceinline__ void pull_elem_staged(const MoveLaunch &ml, const Mov
   // LDS element index of each source inside a staged row, without the row's misalignment; subnets that do not hold
   // the element point at the dummy block
   int off[kChunk][2];
+  int row_step[kChunk][2];  // LDS elements from one staged row to the next: 0 for the dummy block, which is not per row
 #pragma unroll
   for (int i = 0; i < kChunk; ++i)
 #pragma unroll
-    for (int u = 0; u < 2; ++u) off[i][u] = ok[i][u] ? i * SEG + pos[i][u] - lo[i] : DUMMY;
+    for (int u = 0; u < 2; ++u) {
+      off[i][u] = ok[i][u] ? i * SEG + pos[i][u] - lo[i] : DUMMY;
+      row_step[i][u] = ok[i][u] ? kChunk * SEG : 0;
+    }
   // Rows of a subnet tensor that are a multiple of 16 bytes apart (the usual case) all have the misalignment of row
   // 0, which is then folded into the indices once; otherwise it is recomputed for every row.
   const bool same_shift = row_bytes == 0;
@@ -568,7 +575,8 @@ __device__ __forceinline__ void pull_elem_staged(const MoveLaunch &ml, const Mov
       for (int i = 0; i < kChunk; ++i) {
         const int sh = decltype(shift_varies)::value ? (int)(((mis[i] + (uint32_t)row * row_bytes) & 15u) / ES) : 0;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) acc[u] += elem_to_f32<ES>(stage_e[r * kChunk * SEG + off[i][u] + sh]);
+        // largest index: a staged span's last element, or (dummy) DUMMY + sh < DUMMY + VN, inside the two dummy vectors
+        for (int u = 0; u < 2; ++u) acc[u] += elem_to_f32<ES>(stage_e[r * row_step[i][u] + off[i][u] + sh]);
       }
       if (in) {
         E *d = full + row * Wf + v0;
@@ -806,6 +814,17 @@ __global__ __launch_bounds__(kThreads) void to_f32_kernel(const void *src, float
     dst[i] = elem_to_f32<ES>(reinterpret_cast<const E *>(src)[i]);
 }
 
+// bf16 -> fp32, eight values per thread and step: one 16-byte load, two 16-byte stores (a bf16 value is the upper half of
+// the fp32 value with the same bits)
+__global__ __launch_bounds__(kThreads) void bf16_to_f32_vec_kernel(const u32x4 *src, u32x4 *dst, int64_t n_vec) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += stride) {
+    const u32x4 u = __builtin_nontemporal_load(src + i);
+    __builtin_nontemporal_store(u32x4{u.x << 16, u.x & 0xffff0000u, u.y << 16, u.y & 0xffff0000u}, dst + 2 * i);
+    __builtin_nontemporal_store(u32x4{u.z << 16, u.z & 0xffff0000u, u.w << 16, u.w & 0xffff0000u}, dst + 2 * i + 1);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void zero_kernel(u32x4 *dst, int64_t n_vec) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += stride) dst[i] = u32x4{0, 0, 0, 0};
@@ -863,6 +882,13 @@ twist_status twist_launch_accumulate(twist_ctx *ctx, const MoveLaunch &ml, int t
 
 twist_status twist_launch_to_f32(twist_ctx *ctx, const void *src, float *dst, int64_t n) {
   if (n <= 0) return TWIST_OK;
+  if (ctx->esize() == 2 && n % 8 == 0 && (reinterpret_cast<uintptr_t>(src) % 16) == 0 && (reinterpret_cast<uintptr_t>(dst) % 16) == 0) {
+    const int64_t nv = n / 8;
+    const int vblocks = (int)std::min<int64_t>((nv + kThreads - 1) / kThreads, 256 * 16);
+    hipLaunchKernelGGL(bf16_to_f32_vec_kernel, dim3(vblocks), dim3(kThreads), 0, ctx->stream, static_cast<const u32x4 *>(src), reinterpret_cast<u32x4 *>(dst), nv);
+    TW_HIP(ctx, hipGetLastError());
+    return TWIST_OK;
+  }
   int blocks = (int)std::min<int64_t>((n + kThreads - 1) / kThreads, 256 * 16);
   if (ctx->esize() == 2) hipLaunchKernelGGL(to_f32_kernel<2>, dim3(blocks), dim3(kThreads), 0, ctx->stream, src, dst, n);
   else hipLaunchKernelGGL(to_f32_kernel<4>, dim3(blocks), dim3(kThreads), 0, ctx->stream, src, dst, n);

@@ -31,12 +31,15 @@ twist_status twist_gemm(twist_ctx *ctx, int bf16, GemmLayout lay, int M, int N, 
 // causal multi-head attention on a fused qkv buffer [T, 3*Hs*dh] (q | k | v); o [T, Hs*dh]; lse [B,Hs,N] fp32.
 // o32 (may be null): the same output unrounded, [T, Hs*dh] fp32, written by the tiled bf16 kernels only; the
 // tiled backward kernels need it (without it, or on shapes they do not cover, the plain kernels run).
-twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh);
+// keep (may be null; device, one entry per head): heads with keep[h] < 0 are masked (Masked TwIST, Section 4.1): the forward
+// kernels write zeros for them, the backward kernels zero gradients, and neither visits their keys.
+twist_status twist_attention_fwd(twist_ctx *ctx, int bf16, const void *qkv, void *o, float *o32, float *lse, int B, int N, int Hs, int dh,
+                                 const int32_t *keep = nullptr);
 // dqkv [T, 3*Hs*dh] from do [T, Hs*dh]; delta [B,Hs,N] fp32 scratch (sum_j p_ij dp_ij, written by the dq pass).
 // rope_tab (may be null): the table of twist_rope_table; when given, the q and k gradients are also taken back through
 // the rotary embedding (inside the tiled kernels where they cover the shape, else by twist_rope_apply afterwards).
 twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, const float *o32, const void *dout, const float *lse, float *delta,
-                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab);
+                                 void *dqkv, int B, int N, int Hs, int dh, const float *rope_tab, const int32_t *keep = nullptr);
 
 twist_status twist_embed_fwd(twist_ctx *ctx, int bf16, const int32_t *tok, const void *tok_embed, const void *pos_embed, float *x, int B, int N, int D, int vocab);
 twist_status twist_embed_bwd(twist_ctx *ctx, const int32_t *tok, const float *dx, float *d_tok, float *d_pos, int B, int N, int D);
@@ -73,17 +76,17 @@ size_t twist_colsum_partial_floats(int T, int Ncols);
 twist_status twist_rope_table(twist_ctx *ctx, float *tab, int N, int dh, float theta);
 twist_status twist_rope_apply(twist_ctx *ctx, int bf16, void *qkv, const float *tab, int B, int N, int Hs, int dh, float sign);
 
-// act: a = f(u) (gu = [T,F]) or a = silu(g) * u (gu = [T,2F], gate first)
-twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F);
-twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F);
+// act: a = f(u) (gu = [T,F]) or a = silu(g) * u (gu = [T,2F], gate first).
+// keep (may be null; device, one entry per FFN block of `unit` neurons): blocks with keep[b] < 0 are masked (Masked TwIST,
+// Section 4.1): their activations are written as zero and, in the backward kernel, da is taken as zero there.
+twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F, const int32_t *keep = nullptr, int unit = 1);
+twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F, const int32_t *keep = nullptr,
+                           int unit = 1);
 
 // logits [T,V] -> in place dlogits = (softmax - onehot)/T; row losses to rowloss[T]; then loss = mean
 twist_status twist_ce_fwd_bwd(twist_ctx *ctx, int bf16, void *logits, int64_t ld, const int32_t *targets, float *rowloss, float *loss, int T, int V);
 // dx = 2 (x - y)/n ; dxb = activation-type copy; loss = mean squared error
 twist_status twist_mse_fwd_bwd(twist_ctx *ctx, int bf16, const float *x, const void *y, float *dx, void *dxb, float *partial, float *loss, int64_t n);
-
-// x [T, n_units*unit] (activation type): columns of the units u with keep[u] < 0 are set to zero
-twist_status twist_mask_cols(twist_ctx *ctx, int bf16, void *x, const int32_t *keep, int T, int n_units, int unit);
 
 twist_status twist_sgd(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, int64_t n, float lr);
 twist_status twist_adamw(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,

@@ -331,29 +331,34 @@ __device__ __forceinline__ float gelu_tanh_grad(float u) {
 }
 __device__ __forceinline__ float sigmoidf(float x) { return 1.f / (1.f + __expf(-x)); }
 
+// `keep` (may be null): the Masked-TwIST neuron mask of Section 4.1, y = M * f(x).  keep[b] < 0 marks FFN block b (of
+// `unit` neurons) as masked: its activations, and in the backward kernels its pre-activation gradients, are zero.
 template <int BF>
-__global__ __launch_bounds__(kT) void act_fwd_kernel(int act, const void *gu, void *a, int F, int64_t total) {
+__global__ __launch_bounds__(kT) void act_fwd_kernel(int act, const void *gu, void *a, int F, int64_t total, const int32_t *keep, int unit) {
   int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
+  const int64_t t = i / F;
+  const int c = (int)(i - t * F);
+  float o;
   if (act == TWIST_ACT_SWIGLU) {
-    int64_t t = i / F;
-    int c = (int)(i - t * F);
     float g = El<BF>::ld(gu, t * 2 * F + c), u = El<BF>::ld(gu, t * 2 * F + F + c);
-    El<BF>::st(a, i, g * sigmoidf(g) * u);
+    o = g * sigmoidf(g) * u;
   } else {
     float u = El<BF>::ld(gu, i);
-    El<BF>::st(a, i, act == TWIST_ACT_RELU ? fmaxf(u, 0.f) : gelu_tanh(u));
+    o = act == TWIST_ACT_RELU ? fmaxf(u, 0.f) : gelu_tanh(u);
   }
+  if (keep && keep[c / unit] < 0) o = 0.f;
+  El<BF>::st(a, i, o);
 }
 
 template <int BF>
-__global__ __launch_bounds__(kT) void act_bwd_kernel(int act, const void *gu, const void *da, void *dgu, int F, int64_t total) {
+__global__ __launch_bounds__(kT) void act_bwd_kernel(int act, const void *gu, const void *da, void *dgu, int F, int64_t total, const int32_t *keep, int unit) {
   int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
-  const float d = El<BF>::ld(da, i);
+  const int64_t t = i / F;
+  const int c = (int)(i - t * F);
+  const float d = (keep && keep[c / unit] < 0) ? 0.f : El<BF>::ld(da, i);
   if (act == TWIST_ACT_SWIGLU) {
-    int64_t t = i / F;
-    int c = (int)(i - t * F);
     float g = El<BF>::ld(gu, t * 2 * F + c), u = El<BF>::ld(gu, t * 2 * F + F + c);
     float sg = sigmoidf(g);
     El<BF>::st(dgu, t * 2 * F + F + c, d * g * sg);
@@ -425,14 +430,16 @@ __global__ __launch_bounds__(kT) void sgd_kernel(void *params, float *master, co
   }
 }
 
+// `first`: the moments count as zero and are not read (a subnet's first step after extraction).
 template <int BF>
 __global__ __launch_bounds__(kT) void adamw_kernel(void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,
-                                                    float lr, float b1, float b2, float eps, float wd, float inv_bc1, float inv_bc2) {
+                                                    float lr, float b1, float b2, float eps, float wd, float inv_bc1, float inv_bc2, int first) {
   int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= n) return;
   const float g = grads[i];
-  const float mi = b1 * m[i] + (1.f - b1) * g;
-  const float vi = b2 * v[i] + (1.f - b2) * g * g;
+  const float m0 = first ? 0.f : m[i], v0 = first ? 0.f : v[i];
+  const float mi = b1 * m0 + (1.f - b1) * g;
+  const float vi = b2 * v0 + (1.f - b2) * g * g;
   m[i] = mi;
   v[i] = vi;
   float w = BF ? master[i] : static_cast<float *>(params)[i];
@@ -556,7 +563,14 @@ __global__ __launch_bounds__(kT) void ce_vec_long_kernel(u32x4v *logits, int64_t
 }
 
 // a = silu(g) * u on [T, 2F] (gate | up) -> [T, F]; i8 runs over T * F/8
-__global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u32x4v *a, int F8n, int64_t total) {
+// multiplies the 8 values of columns col0 .. col0 + 7 by the block mask (see act_fwd_kernel)
+__device__ __forceinline__ void mask8(F8 &x, const int32_t *keep, int unit, int col0) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    if (keep[(col0 + e) / unit] < 0) x.v[e] = 0.f;
+}
+
+__global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u32x4v *a, int F8n, int64_t total, const int32_t *keep, int unit) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
   const int64_t t = i / F8n;
@@ -565,36 +579,45 @@ __global__ __launch_bounds__(kT) void swiglu_fwd_vec_kernel(const u32x4v *gu, u3
   F8 o;
 #pragma unroll
   for (int e = 0; e < 8; ++e) o.v[e] = g.v[e] * sigmoidf(g.v[e]) * u.v[e];
+  if (keep) mask8(o, keep, unit, 8 * c);
   a[i] = pack8(o);
 }
 
 // ungated activations (GELU, ReLU), eight values per thread
-__global__ __launch_bounds__(kT) void act_fwd_vec_kernel(int act, const u32x4v *u, u32x4v *a, int64_t total) {
+// F8n = F / 8 (a row's 8-column groups) where a mask is given, so that a thread knows its columns
+__global__ __launch_bounds__(kT) void act_fwd_vec_kernel(int act, const u32x4v *u, u32x4v *a, int64_t total, const int32_t *keep, int unit, int F8n) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
   const F8 x = unpack8(u[i]);
   F8 o;
 #pragma unroll
   for (int e = 0; e < 8; ++e) o.v[e] = act == TWIST_ACT_RELU ? fmaxf(x.v[e], 0.f) : gelu_tanh(x.v[e]);
+  if (keep) mask8(o, keep, unit, 8 * (int)(i % F8n));
   a[i] = pack8(o);
 }
 
-__global__ __launch_bounds__(kT) void act_bwd_vec_kernel(int act, const u32x4v *u, const u32x4v *da, u32x4v *du, int64_t total) {
+__global__ __launch_bounds__(kT) void act_bwd_vec_kernel(int act, const u32x4v *u, const u32x4v *da, u32x4v *du, int64_t total, const int32_t *keep, int unit,
+                                                          int F8n) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
-  const F8 x = unpack8(u[i]), d = unpack8(da[i]);
+  const F8 x = unpack8(u[i]);
+  F8 d = unpack8(da[i]);
+  if (keep) mask8(d, keep, unit, 8 * (int)(i % F8n));
   F8 o;
 #pragma unroll
   for (int e = 0; e < 8; ++e) o.v[e] = d.v[e] * (act == TWIST_ACT_RELU ? (x.v[e] > 0.f ? 1.f : 0.f) : gelu_tanh_grad(x.v[e]));
   du[i] = pack8(o);
 }
 
-__global__ __launch_bounds__(kT) void swiglu_bwd_vec_kernel(const u32x4v *gu, const u32x4v *da, u32x4v *dgu, int F8n, int64_t total) {
+__global__ __launch_bounds__(kT) void swiglu_bwd_vec_kernel(const u32x4v *gu, const u32x4v *da, u32x4v *dgu, int F8n, int64_t total, const int32_t *keep,
+                                                             int unit) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
   const int64_t t = i / F8n;
   const int c = (int)(i - t * F8n);
-  const F8 g = unpack8(gu[t * 2 * F8n + c]), u = unpack8(gu[t * 2 * F8n + F8n + c]), d = unpack8(da[i]);
+  const F8 g = unpack8(gu[t * 2 * F8n + c]), u = unpack8(gu[t * 2 * F8n + F8n + c]);
+  F8 d = unpack8(da[i]);
+  if (keep) mask8(d, keep, unit, 8 * c);
   F8 dg, du;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -670,14 +693,6 @@ __global__ __launch_bounds__(kT) void norm_fwd_vec_kernel(const float *x, const 
     static_cast<u2 *>(y)[rv + lane + 64 * k] = pk;
   }
   if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
-}
-
-template <int BF>
-__global__ __launch_bounds__(kT) void mask_cols_kernel(void *x, const int32_t *keep, int ncols, int unit, int64_t total) {
-  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (i >= total) return;
-  const int c = (int)(i % ncols);
-  if (keep[c / unit] < 0) El<BF>::st(x, i, 0.f);
 }
 
 inline dim3 grid1(int64_t n) { return dim3((unsigned)((n + kT - 1) / kT)); }
@@ -845,37 +860,39 @@ twist_status twist_rope_apply(twist_ctx *ctx, int bf16, void *qkv, const float *
   return TWIST_OK;
 }
 
-twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F) {
+twist_status twist_act_fwd(twist_ctx *ctx, int bf16, int act, const void *gu, void *a, int T, int F, const int32_t *keep, int unit) {
   const int64_t total = (int64_t)T * F;
   if (bf16 && act == TWIST_ACT_SWIGLU && F % 8 == 0 && al16(gu) && al16(a)) {
-    hipLaunchKernelGGL(swiglu_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), F / 8, total / 8);
+    hipLaunchKernelGGL(swiglu_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), F / 8, total / 8,
+                       keep, unit);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
-  if (bf16 && act != TWIST_ACT_SWIGLU && total % 8 == 0 && al16(gu) && al16(a)) {
-    hipLaunchKernelGGL(act_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, act, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), total / 8);
+  if (bf16 && act != TWIST_ACT_SWIGLU && (keep ? F % 8 == 0 : total % 8 == 0) && al16(gu) && al16(a)) {
+    hipLaunchKernelGGL(act_fwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, act, static_cast<const u32x4v *>(gu), static_cast<u32x4v *>(a), total / 8,
+                       keep, unit, F / 8);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
-  LAUNCH_BF(act_fwd_kernel, bf16, grid1(total), dim3(kT), act, gu, a, F, total);
+  LAUNCH_BF(act_fwd_kernel, bf16, grid1(total), dim3(kT), act, gu, a, F, total, keep, unit);
   return TWIST_OK;
 }
 
-twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F) {
+twist_status twist_act_bwd(twist_ctx *ctx, int bf16, int act, const void *gu, const void *da, void *dgu, int T, int F, const int32_t *keep, int unit) {
   const int64_t total = (int64_t)T * F;
   if (bf16 && act == TWIST_ACT_SWIGLU && F % 8 == 0 && al16(gu) && al16(da) && al16(dgu)) {
     hipLaunchKernelGGL(swiglu_bwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, static_cast<const u32x4v *>(gu), static_cast<const u32x4v *>(da),
-                       static_cast<u32x4v *>(dgu), F / 8, total / 8);
+                       static_cast<u32x4v *>(dgu), F / 8, total / 8, keep, unit);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
-  if (bf16 && act != TWIST_ACT_SWIGLU && total % 8 == 0 && al16(gu) && al16(da) && al16(dgu)) {
+  if (bf16 && act != TWIST_ACT_SWIGLU && (keep ? F % 8 == 0 : total % 8 == 0) && al16(gu) && al16(da) && al16(dgu)) {
     hipLaunchKernelGGL(act_bwd_vec_kernel, grid1(total / 8), dim3(kT), 0, ctx->stream, act, static_cast<const u32x4v *>(gu), static_cast<const u32x4v *>(da),
-                       static_cast<u32x4v *>(dgu), total / 8);
+                       static_cast<u32x4v *>(dgu), total / 8, keep, unit, F / 8);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
-  LAUNCH_BF(act_bwd_kernel, bf16, grid1(total), dim3(kT), act, gu, da, dgu, F, total);
+  LAUNCH_BF(act_bwd_kernel, bf16, grid1(total), dim3(kT), act, gu, da, dgu, F, total, keep, unit);
   return TWIST_OK;
 }
 
@@ -908,12 +925,6 @@ twist_status twist_sgd(twist_ctx *ctx, int bf16, void *params, float *master, co
 twist_status twist_adamw(twist_ctx *ctx, int bf16, void *params, float *master, const float *grads, float *m, float *v, int64_t n, int64_t n_decay,
                          float lr, float b1, float b2, float eps, float wd, int64_t step) {
   const double bc1 = 1.0 - pow((double)b1, (double)step), bc2 = 1.0 - pow((double)b2, (double)step);
-  LAUNCH_BF(adamw_kernel, bf16, grid1(n), dim3(kT), params, master, grads, m, v, n, n_decay, lr, b1, b2, eps, wd, (float)(1.0 / bc1), (float)(1.0 / bc2));
-  return TWIST_OK;
-}
-
-twist_status twist_mask_cols(twist_ctx *ctx, int bf16, void *x, const int32_t *keep, int T, int n_units, int unit) {
-  const int64_t total = (int64_t)T * n_units * unit;
-  LAUNCH_BF(mask_cols_kernel, bf16, grid1(total), dim3(kT), x, keep, n_units * unit, unit, total);
+  LAUNCH_BF(adamw_kernel, bf16, grid1(n), dim3(kT), params, master, grads, m, v, n, n_decay, lr, b1, b2, eps, wd, (float)(1.0 / bc1), (float)(1.0 / bc2), step == 1 ? 1 : 0);
   return TWIST_OK;
 }

@@ -172,17 +172,20 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
   const bool um = d.out_unit_major != 0;  // output projections stored [in, out]: the three GEMM forms rotate
   // Masked variant (Section 4.1, "Masked TwIST"): `sub` is a full-width subnet and the blocks that row `mask_row` of
   // `mask_plan` does not name are zeroed where they enter the output projections (attention output columns,
-  // FFN activations) and where the gradient comes back through the same places; the module scales are those of
-  // the masked widths.  Everything else is the ordinary pass.
+  // FFN activations) and where the gradient comes back through the same places, inside the kernels that produce
+  // those tensors (attention forward / backward, activation forward / backward); the module scales are those of
+  // the masked widths.  Everything else is the ordinary pass, with the same number of launches.
   if (mask_plan) {
     for (int l = 0; l < d.n_layers; ++l)
       if (L.heads_sub[l] != d.n_heads || L.ffn_sub[l] != ctx->n_ffn_units())
         TW_FAIL(ctx, TWIST_ESHAPE, "masked pass: the subnet must hold every block of layer %d", l);
   }
-  auto mask = [&](void *x, int l, int kind, int unit) -> twist_status {  // zero the columns of x [T, n_full*unit] of blocks not kept
-    if (!mask_plan) return TWIST_OK;
+  // per-block mask of layer l (device table: entry < 0 = block not kept), handed to the kernels that produce the attention
+  // output, the FFN activation and their gradients; null in the ordinary pass
+  auto keep_of = [&](int l, int kind) -> const int32_t * {
+    if (!mask_plan) return nullptr;
     const PlanEntry &pe = mask_plan->at(l, kind);
-    return twist_mask_cols(ctx, bf, x, pe.d_inv + (size_t)mask_row * pe.n_full, T, pe.n_full, unit);
+    return pe.d_inv + (size_t)mask_row * pe.n_full;
   };
   auto kept = [&](int l, int kind, int full) { return mask_plan ? mask_plan->at(l, kind).n_sub : full; };
   const int scale_mode = mask_plan ? mask_plan->scale_mode : sub->plan->scale_mode;
@@ -222,15 +225,13 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l], P(L.at(l, TWIST_NORM1_W)), P(L.at(l, TWIST_NORM1_B)), b.h1, w.stats[2 * l], T, D, d.norm_eps));
     TW_TRY(gemm(GEMM_NT, T, 3 * HD, D, b.h1, D, P(L.at(l, TWIST_WQ)), D, b.qkv, 3 * HD, 0, 1.f, P(L.at(l, TWIST_BQ))));
     if (d.use_rope) TW_TRY(twist_rope_apply(ctx, bf, b.qkv, w.rope_tab, B, N, Hs, dh, 1.f));
-    TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.o32, b.lse, B, N, Hs, dh));
-    TW_TRY(mask(b.o, l, TWIST_KIND_HEAD, dh));
+    TW_TRY(twist_attention_fwd(ctx, bf, b.qkv, b.o, b.o32, b.lse, B, N, Hs, dh, keep_of(l, TWIST_KIND_HEAD)));
     if (um) TW_TRY(gemm(GEMM_NN, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), D, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     else TW_TRY(gemm(GEMM_NT, T, D, HD, b.o, HD, P(L.at(l, TWIST_WO)), HD, w.xs[2 * l + 1], D, 1, c_a, P(L.at(l, TWIST_BO)), w.xs[2 * l]));
     TW_TRY(twist_norm_fwd(ctx, bf, rms, w.xs[2 * l + 1], P(L.at(l, TWIST_NORM2_W)), P(L.at(l, TWIST_NORM2_B)), b.h2, w.stats[2 * l + 1], T, D, d.norm_eps));
     const Slot &w1 = nf == 2 ? L.at(l, TWIST_W_GATE) : L.at(l, TWIST_W_UP);
     TW_TRY(gemm(GEMM_NT, T, nf * F, D, b.h2, D, P(w1), D, b.gu, nf * F, 0, 1.f, P(L.at(l, TWIST_B_UP))));
-    TW_TRY(twist_act_fwd(ctx, bf, d.act, b.gu, b.a, T, F));
-    TW_TRY(mask(b.a, l, TWIST_KIND_FFN, d.ffn_granule));
+    TW_TRY(twist_act_fwd(ctx, bf, d.act, b.gu, b.a, T, F, keep_of(l, TWIST_KIND_FFN), d.ffn_granule));
     if (um) TW_TRY(gemm(GEMM_NN, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), D, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
     else TW_TRY(gemm(GEMM_NT, T, D, F, b.a, F, P(L.at(l, TWIST_W_DOWN)), F, w.xs[2 * l + 2], D, 1, c_f, P(L.at(l, TWIST_B_DOWN)), w.xs[2 * l + 1]));
   }
@@ -287,9 +288,8 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.done(0));
     if (um) TW_TRY(gemm(GEMM_NT, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), D, w.da, F, 0, c_f));
     else TW_TRY(gemm(GEMM_NN, T, F, D, gx, D, P(L.at(l, TWIST_W_DOWN)), F, w.da, F, 0, c_f));
-    TW_TRY(mask(w.da, l, TWIST_KIND_FFN, d.ffn_granule));
     TW_TRY(side.wait_done(1));
-    TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F));
+    TW_TRY(twist_act_bwd(ctx, bf, d.act, b.gu, w.da, w.dgu, T, F, keep_of(l, TWIST_KIND_FFN), d.ffn_granule));
     if (L.at(l, TWIST_B_UP).off >= 0) TW_TRY(bias_grad(w.dgu, nf * F, 1.f, G(L.at(l, TWIST_B_UP)), nf * F));
     TW_TRY(side.fork(1));
     TW_TRY(wgrad(nf * F, D, w.dgu, nf * F, b.h2, D, G(w1), 1.f));
@@ -305,9 +305,9 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     TW_TRY(side.done(2));
     if (um) TW_TRY(gemm(GEMM_NT, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), D, w.dout, HD, 0, c_a));
     else TW_TRY(gemm(GEMM_NN, T, HD, D, gx_other, D, P(L.at(l, TWIST_WO)), HD, w.dout, HD, 0, c_a));
-    TW_TRY(mask(w.dout, l, TWIST_KIND_HEAD, dh));
     TW_TRY(side.wait_done(3));
-    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh, d.use_rope ? w.rope_tab : nullptr));
+    TW_TRY(twist_attention_bwd(ctx, bf, b.qkv, b.o32, w.dout, b.lse, w.delta, w.dqkv, B, N, Hs, dh, d.use_rope ? w.rope_tab : nullptr,
+                               keep_of(l, TWIST_KIND_HEAD)));
     if (L.at(l, TWIST_BQ).off >= 0) TW_TRY(bias_grad(w.dqkv, 3 * HD, 1.f, G(L.at(l, TWIST_BQ)), 3 * HD));
     TW_TRY(side.fork(3));
     TW_TRY(wgrad(3 * HD, D, w.dqkv, 3 * HD, b.h1, D, G(L.at(l, TWIST_WQ)), 1.f));

@@ -71,6 +71,10 @@ struct twist_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_ready[4] = {}, ev_done[4] = {};
   bool overlap = true;
+  // kernel selection overrides for tests (twist_set_kernel_choice); the defaults let every launcher choose by shape
+  int gemm_tile = 0;         // 0 = by shape; 128 / 256 pin the matrix-core projection kernel's tile (and keep the contraction whole)
+  bool plain_only = false;   // never use the matrix-core kernels (projections and attention run the plain fp32-arithmetic ones)
+  bool staged_attention = false;  // d_head 128: the register-staged tiled attention kernels instead of the direct-to-LDS ones
   int esize() const { return d.dtype == TWIST_BF16 ? 2 : 4; }
   int n_ffn_units() const { return d.d_ff / d.ffn_granule; }
 };

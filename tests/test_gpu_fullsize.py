@@ -1,5 +1,6 @@
 """Full-size checks on the GPU, in the launch configurations bench.py times (Llama-1B-shaped workload: d = 2048,
-8 of 16 heads x 128, F' = 2816 of 5632, vocabulary 32000, batch 4 x 2048).  The fp64 checker cannot run that shape
+8 of 16 heads x 128, F' = 2816 of 5632, vocabulary 32000, batch 4 x 2048; Llama-7B-shaped pruned-once workload: d = 4096,
+16 of 32 heads x 128, F' = 5504 of 11008, batch 2 x 4096).  The fp64 checker cannot run those shapes
 end to end in test time, so the kernels are checked where they can be: sampled entries of every projection
 against plain fp64 dot products, sampled heads of the attention kernels against the checker's attention, and a
 property of the whole pass (weight gradients computed on the second stream are bit-identical to the serial
@@ -24,9 +25,18 @@ PROJECTIONS = [  # (name, layout, M, N, K) of one layer of the subnet and of the
     ("down dgrad", 0, T, 2816, 2048), ("head dgrad", 1, T, 2048, 32000), ("qkv wgrad", 2, 3072, 2048, T), ("o wgrad", 2, 1024, 2048, T),
     ("gate/up wgrad", 2, 5632, 2048, T), ("down wgrad", 2, 2816, 2048, T), ("head wgrad", 2, 32000, 2048, T),
 ]
+# the pruned Llama-7B-shaped layer (d 4096, attention width 2048, F' 5504) and, last two, the longest contractions of the
+# unpruned one (down projection over 11008 neurons, gate/up input gradient over 2 x 11008)
+PROJECTIONS_7B = [
+    ("7b qkv fwd", 0, T, 6144, 4096), ("7b o fwd", 1, T, 4096, 2048), ("7b gate/up fwd", 0, T, 11008, 4096), ("7b down fwd", 1, T, 4096, 5504),
+    ("7b head fwd", 0, T, 32000, 4096), ("7b qkv dgrad", 1, T, 4096, 6144), ("7b o dgrad", 0, T, 2048, 4096), ("7b gate/up dgrad", 1, T, 4096, 11008),
+    ("7b down dgrad", 0, T, 5504, 4096), ("7b head dgrad", 1, T, 4096, 32000), ("7b qkv wgrad", 2, 6144, 4096, T), ("7b o wgrad", 2, 2048, 4096, T),
+    ("7b gate/up wgrad", 2, 11008, 4096, T), ("7b down wgrad", 2, 5504, 4096, T), ("7b head wgrad", 2, 32000, 4096, T),
+    ("7b unpruned down fwd", 1, T, 4096, 11008), ("7b unpruned gate/up dgrad", 1, T, 4096, 22016),
+]
 
 
-@pytest.mark.parametrize("name,layout,M,N,K", PROJECTIONS)
+@pytest.mark.parametrize("name,layout,M,N,K", PROJECTIONS + PROJECTIONS_7B)
 def test_projection_at_bench_shape_sampled_entries(lib, name, layout, M, N, K):
     ctx = lib.Context(lib.desc_from_cfg(si.CFG3))
     gen = torch.Generator(device="cuda").manual_seed(M + 3 * N + 7 * K + layout)
@@ -51,19 +61,21 @@ def test_projection_at_bench_shape_sampled_entries(lib, name, layout, M, N, K):
         assert not torch.isnan(out[-1]).any() and not torch.isnan(out[:, -1]).any()   # the edges were written
 
 
-def test_attention_at_bench_shape_sampled_heads(lib):
-    """B = 4, N = 2048, 8 heads of 128: forward output, log-sum-exp and the three input gradients of sampled heads
-    against the checker's attention in fp64 on the same bf16 inputs."""
+@pytest.mark.parametrize("B,N,Hs,picks", [(4, 2048, 8, ((0, 0), (2, 5), (3, 7))), (2, 4096, 16, ((0, 3), (1, 15)))])
+def test_attention_at_bench_shape_sampled_heads(lib, B, N, Hs, picks):
+    """B = 4, N = 2048, 8 heads of 128 (Llama-1B-shaped subnet) and B = 2, N = 4096, 16 heads (pruned Llama-7B-shaped
+    stack): forward output, log-sum-exp and the three input gradients of sampled heads against the checker's attention
+    in fp64 on the same bf16 inputs."""
     cfg = si.CFG3
-    B, N, Hs, dh = 4, 2048, 8, cfg.d_head
+    dh = cfg.d_head
     ctx = lib.Context(lib.desc_from_cfg(cfg))
-    gen = torch.Generator(device="cuda").manual_seed(17)
+    gen = torch.Generator(device="cuda").manual_seed(17 + N)
     qkv = torch.randn((B * N, 3 * Hs * dh), generator=gen, device="cuda").to(torch.bfloat16)
     dout = torch.randn((B * N, Hs * dh), generator=gen, device="cuda").to(torch.bfloat16)
     o, lse, dqkv = ctx.twist_attention_raw(qkv, dout, B, N, Hs)
     torch.cuda.synchronize()
     HD = Hs * dh
-    for b, h in ((0, 0), (2, 5), (3, 7)):
+    for b, h in picks:
         rows = slice(b * N, (b + 1) * N)
         pick = lambda t, part: to_numpy(t[rows, part * HD + h * dh: part * HD + (h + 1) * dh]).reshape(1, N, 1, dh)
         q, k, v = pick(qkv, 0), pick(qkv, 1), pick(qkv, 2)
@@ -120,13 +132,10 @@ def test_second_stream_weight_gradients_are_bit_identical_to_serial_schedule(lib
     # The weight gradients above were computed with the token dimension cut into parts (few output tiles, 8192 tokens).
     # The same pass with that disabled (every projection on the 256x256-tile kernel, one contraction) must agree to
     # fp32 summation-order accuracy.
-    import os
-    os.environ["TWIST_GEMM_TILE"] = "256"
-    try:
-        ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
-        torch.cuda.synchronize()
-    finally:
-        del os.environ["TWIST_GEMM_TILE"]
+    ctx.twist_set_kernel_choice(gemm_tile=256)
+    ctx.twist_subnet_fwd_bwd(sub, x, y, ws, loss)
+    torch.cuda.synchronize()
+    ctx.twist_set_kernel_choice()
     for l in range(cfg.n_layers):
         for k in ("wq", "wo", "w_gate", "w_down"):
             g0, g1 = results[0][1][(l, k)], sub.twist_subnet_view(l, k, 1)

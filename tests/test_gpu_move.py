@@ -47,9 +47,10 @@ def test_sample_matches_oracle_bit_exactly(lib, case):
                 assert idx.tolist() == w["idx"], (l, kind)
                 assert inv.tolist() == w["inv"]
                 assert cnt.tolist() == w["count"]
-                # the device copies hold the same integers
-                d_idx, d_inv, d_cnt, ns, nf = plan.device_tables(l, kind)
-                assert (ns, nf) == (w["n_sub"], w["n_full"])
+                # the device copies, read back, hold the same integers
+                d_idx, d_inv, d_cnt = plan.twist_plan_read_device(l, kind)
+                assert d_idx.tolist() == w["idx"] and d_inv.tolist() == w["inv"] and d_cnt.tolist() == w["count"], (l, kind)
+                assert plan.device_tables(l, kind)[3:] == (w["n_sub"], w["n_full"])
         plan.close()
 
 
@@ -318,6 +319,37 @@ def test_movers_on_a_seeded_sweep_of_ragged_shapes(lib):
             assert torch.equal(full_t["globals"][k].view(torch.uint8), other_t["globals"][k].view(torch.uint8)), (tag, k)
         acc.close()
         ctx.close()
+
+
+@pytest.mark.parametrize("name", ["ragged_bf16", "wide_odd_bf16", "wide_odd_f32", "llama_overlap_S8", "gpt_bf16", "llama_bf16_um"])
+def test_single_owner_copy_keeps_the_sign_of_zero(lib, name):
+    """A parameter with one owner is copied bit for bit (Section 3.3 with a one-term sum): every subnet value is set to
+    -0.0, so each single-owner element of the central model must come back with the sign bit set, in every row of the
+    tensor and also where subnets that do not hold the block come before the owner in the sum."""
+    cfg, S, full_np, full_t, ctx, plan, oplan, fw = _setup(lib, name, seed=13)
+    subs = [ctx.twist_extract(plan, fw, s) for s in range(S)]
+    for sub in subs:
+        for l in range(cfg.n_layers):
+            for k in si.layer_shapes(cfg):
+                sub.twist_subnet_view(l, k).fill_(-0.0)
+    ctx.twist_aggregate(plan, subs, fw)
+    torch.cuda.synchronize()
+    bits = torch.int16 if cfg.dtype == "bf16" else torch.int32
+    checked = 0
+    for l in range(cfg.n_layers):
+        for k, (kind, axis) in omove.PARTITIONED.items():
+            if k not in full_t["layers"][l]:
+                continue
+            q = cfg.d_head if kind == 0 else cfg.ffn_granule
+            single = np.repeat(np.array(oplan[l][kind]["count"]) == 1, q)
+            if not single.any():
+                continue
+            stored_axis = 0 if cfg.out_unit_major and k in si.STORED_TRANSPOSED else axis
+            t = full_t["layers"][l][k].view(bits).cpu().numpy()
+            sel = t[single] if stored_axis == 0 else t[:, single]
+            assert (sel == np.iinfo(sel.dtype).min).all(), (name, l, k)      # sign bit only: -0.0
+            checked += sel.size
+    assert checked > 0
 
 
 def test_untrained_partition_roundtrip_is_bit_exact(lib):
