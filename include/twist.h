@@ -272,10 +272,14 @@ TWIST_API twist_status twist_gemm_raw(twist_ctx *ctx, int32_t layout, int32_t M,
  * Outputs: o [B*N, Hs*d_head] (desc.dtype), lse [B, Hs, N] fp32 (log-sum-exp of the scaled scores), and dqkv
  * [B*N, 3*Hs*d_head] from dout [B*N, Hs*d_head].  o32 [B*N, Hs*d_head] fp32 and delta [B, Hs, N] fp32 are
  * caller-provided scratch (o32 receives the unrounded output of bf16 models).  keep (dev int32 [Hs], may be NULL) is the
- * head mask of Masked TwIST (Section 4.1): heads with keep[h] < 0 give zero output and zero gradients.  All device
- * pointers, caller-owned; work is enqueued on the ctx's stream.  TWIST_ESHAPE if d_head exceeds 256. */
+ * head mask of Masked TwIST (Section 4.1): heads with keep[h] < 0 give zero output and zero gradients.  rope_tab (scratch
+ * of N * d_head floats, may be NULL): when given, q and k are taken to be already rotated by the rotary embedding and
+ * their gradients in dqkv are turned back through it, as the training pass does (inside the attention kernels where they
+ * cover the shape).  All device pointers, caller-owned; work is enqueued on the ctx's stream.  TWIST_ESHAPE if d_head
+ * exceeds 256. */
 TWIST_API twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs,
-                                           void *o, float *o32, float *lse, float *delta, void *dqkv, const int32_t *keep);
+                                           void *o, float *o32, float *lse, float *delta, void *dqkv, const int32_t *keep,
+                                           float *rope_tab);
 
 /* Kernel-level entry points for tests: the memory-bound steps of twist_subnet_fwd_bwd in isolation, run by the same
  * kernels, on the ctx's stream.  Shapes and kinds come from the ctx's model description (d_model, d_head, norm, act,

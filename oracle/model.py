@@ -35,8 +35,10 @@ def _ident(tag, a):
 # Every tensor class the rounding hook is offered, i.e. every place where a bf16 model stores an activation or an
 # activation gradient between two kernels: normed inputs (h1, h2, hf), projections of them (qkv, also after the rotary
 # embedding; u: FFN pre-activations, gate included), attention output (o), FFN activation (a), logits; backward: the
-# loss gradient (dlogits), the residual-stream gradient handed to a module (dres) and every activation gradient (dact).
-HOOK_TAGS = ("h1", "qkv", "o", "h2", "u", "a", "hf", "logits", "dlogits", "dres", "dact")
+# loss gradient (dlogits), the residual-stream gradient handed to a module (dres) and every activation gradient (dact);
+# and the two tensors a tiled attention kernel hands to the matrix cores in bf16 without ever storing them: the
+# probabilities (p, forward and in the value gradient) and the score gradient (ds).
+HOOK_TAGS = ("h1", "qkv", "p", "o", "h2", "u", "a", "hf", "logits", "dlogits", "dres", "dact", "ds")
 
 
 # ----------------------------------------------------------------------------- pieces
@@ -147,9 +149,12 @@ def rope_apply(x, cos, sin, sign=1.0):
 
 
 # ----------------------------------------------------------------------------- model
-def attention_fwd(qh, kh, vh):
+def attention_fwd(qh, kh, vh, q=_ident):
     """Causal multi-head attention of Appendix A.1 on [B, N, H, d_head] arrays: softmax(Q K^T / sqrt(d_head)) V
-    per head with keys after the query masked out.  Returns (output [B, N, H, d_head], probabilities [B, H, N, N])."""
+    per head with keys after the query masked out.  Returns (output [B, N, H, d_head], probabilities [B, H, N, N]).
+    A rounding hook is offered the probabilities ("p"); rounded probabilities are renormalised to sum to one, so that
+    the output stays a convex combination of the value rows (what a kernel that feeds rounded probabilities to the
+    matrix cores and divides by their sum computes)."""
     N, dh = qh.shape[1], qh.shape[3]
     causal = np.triu(np.ones((N, N), dtype=bool), k=1)
     sc = np.einsum("bnhe,bmhe->bhnm", qh, kh) / math.sqrt(dh)
@@ -157,15 +162,20 @@ def attention_fwd(qh, kh, vh):
     sc = sc - sc.max(-1, keepdims=True)
     p = np.exp(sc)
     p = p / p.sum(-1, keepdims=True)
+    pr = q("p", p)
+    if pr is not p:
+        p = pr / pr.sum(-1, keepdims=True)
     return np.einsum("bhnm,bmhe->bnhe", p, vh), p
 
 
-def attention_bwd(p, qh, kh, vh, do):
-    """Gradients of attention_fwd's output with respect to q, k, v given d(output) = do (all [B, N, H, d_head])."""
+def attention_bwd(p, qh, kh, vh, do, q=_ident):
+    """Gradients of attention_fwd's output with respect to q, k, v given d(output) = do (all [B, N, H, d_head]).
+    A rounding hook is offered the probabilities where they enter the value gradient ("p") and the score gradient
+    where it enters the query and key gradients ("ds")."""
     dh = qh.shape[3]
-    dv = np.einsum("bhnm,bnhe->bmhe", p, do)
+    dv = np.einsum("bhnm,bnhe->bmhe", q("p", p), do)
     dp = np.einsum("bnhe,bmhe->bhnm", do, vh)
-    ds = p * (dp - (dp * p).sum(-1, keepdims=True)) / math.sqrt(dh)
+    ds = q("ds", p * (dp - (dp * p).sum(-1, keepdims=True)) / math.sqrt(dh))
     dq = np.einsum("bhnm,bmhe->bnhe", ds, kh)
     dk = np.einsum("bhnm,bnhe->bmhe", ds, qh)
     return dq, dk, dv
@@ -208,7 +218,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
         qh, kh, vh = (q("qkv", t).reshape(B, N, Hs, dh) for t in (qh, kh, vh))
         if cfg.rope:
             qh, kh = q("qkv", rope_apply(qh, cos, sin)), q("qkv", rope_apply(kh, cos, sin))
-        o, p = attention_fwd(qh, kh, vh)
+        o, p = attention_fwd(qh, kh, vh, q)
         o = q("o", o.reshape(B, N, Hs * dh))
         c.update(q=qh, k=kh, v=vh, p=p, o=o)
         y = o @ lw["wo"].T + lw.get("bo", 0.0)
@@ -299,7 +309,7 @@ def forward_backward(cfg, P, inputs, targets, scale_mode=True, q=_ident, need_gr
             g_["bo"] = dyf.sum(0)
         do = q("dact", dy @ lw["wo"]).reshape(B, N, Hs, dh)
         p, qh, kh, vh = c["p"], c["q"], c["k"], c["v"]
-        dq, dk, dv = attention_bwd(p, qh, kh, vh, do)
+        dq, dk, dv = attention_bwd(p, qh, kh, vh, do, q)
         if cfg.rope:
             dq, dk = q("dact", dq), q("dact", dk)      # rounding point only; identity by default
             dq, dk = rope_apply(dq, cos, sin, -1.0), rope_apply(dk, cos, sin, -1.0)

@@ -96,7 +96,7 @@ _SIGS = {
     "twist_round_bytes": ([_vp, C.POINTER(RoundDesc), C.POINTER(_sz), C.POINTER(_sz), C.POINTER(_sz)], _i32),
     "twist_round": ([_vp, C.POINTER(RoundDesc), C.POINTER(FullWeightsC), _vp, _vp, _vp, _sz, _vp, _sz, _vp, _sz, _vp], _i32),
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
-    "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
+    "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
     "twist_norm_raw": ([_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz], _i32),
     "twist_rope_raw": ([_vp, _vp, _i32, _i32, _i32, C.c_float, _vp], _i32),
     "twist_act_raw": ([_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32], _i32),
@@ -260,9 +260,10 @@ class Context:
                                   _vp(out.data_ptr()), out.stride(0), int(out.dtype == torch.float32 and self.torch_dtype != torch.float32
                                                                           or out.dtype == torch.float32), alpha), self.h)
 
-    def twist_attention_raw(self, qkv: torch.Tensor, dout, B: int, N: int, Hs: int, keep: torch.Tensor | None = None):
+    def twist_attention_raw(self, qkv: torch.Tensor, dout, B: int, N: int, Hs: int, keep: torch.Tensor | None = None, rope_backward: bool = False):
         """Causal attention alone: returns (o, lse, dqkv or None) for qkv [B*N, 3*Hs*d_head] and dout [B*N, Hs*d_head] or None;
-        keep: int32 [Hs] head mask (entries < 0 are masked) or None."""
+        keep: int32 [Hs] head mask (entries < 0 are masked) or None; rope_backward: the q and k gradients are also turned
+        back through the rotary embedding."""
         T, HD = B * N, qkv.shape[1] // 3
         o = torch.empty((T, HD), dtype=qkv.dtype, device=qkv.device)
         o32 = torch.empty((T, HD), dtype=torch.float32, device=qkv.device)
@@ -271,7 +272,8 @@ class Context:
         dqkv = torch.empty_like(qkv) if dout is not None else None
         _check(lib.twist_attention_raw(self.h, _vp(qkv.data_ptr()), _vp(dout.data_ptr()) if dout is not None else None, B, N, Hs,
                                        _vp(o.data_ptr()), _vp(o32.data_ptr()), _vp(lse.data_ptr()), _vp(delta.data_ptr()),
-                                       _vp(dqkv.data_ptr()) if dqkv is not None else None, _ptr(keep)), self.h)
+                                       _vp(dqkv.data_ptr()) if dqkv is not None else None, _ptr(keep),
+                                       _ptr(torch.empty(N * self.desc.d_head, dtype=torch.float32, device=qkv.device)) if rope_backward else None), self.h)
         return o, lse, dqkv
 
     def twist_norm_raw(self, x: torch.Tensor, w: torch.Tensor, b, dy=None):

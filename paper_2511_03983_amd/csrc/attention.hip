@@ -219,14 +219,18 @@ twist_status twist_attention_bwd(twist_ctx *ctx, int bf16, const void *qkv, cons
 }
 
 extern "C" twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, const void *dout, int32_t B, int32_t N, int32_t Hs, void *o, float *o32,
-                                            float *lse, float *delta, void *dqkv, const int32_t *keep) {
+                                            float *lse, float *delta, void *dqkv, const int32_t *keep, float *rope_tab) {
   if (!ctx || !qkv || !o || !o32 || !lse) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: null argument");
   if (B < 1 || N < 1 || Hs < 1) TW_FAIL(ctx, TWIST_ESHAPE, "twist_attention_raw: empty shape");
   const int bf = ctx->d.dtype == TWIST_BF16;
   TW_TRY(twist_attention_fwd(ctx, bf, qkv, o, o32, lse, B, N, Hs, ctx->d.d_head, keep));
   if (dout) {
     if (!delta || !dqkv) TW_FAIL(ctx, TWIST_EINVAL, "twist_attention_raw: backward needs delta and dqkv");
-    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head, nullptr, keep));
+    if (rope_tab) {
+      if (ctx->d.d_head % 2) TW_FAIL(ctx, TWIST_ESHAPE, "twist_attention_raw: rotary positions need an even d_head");
+      TW_TRY(twist_rope_table(ctx, rope_tab, N, ctx->d.d_head, ctx->d.rope_theta));
+    }
+    TW_TRY(twist_attention_bwd(ctx, bf, qkv, o32, dout, lse, delta, dqkv, B, N, Hs, ctx->d.d_head, rope_tab, keep));
   }
   return TWIST_OK;
 }

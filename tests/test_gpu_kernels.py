@@ -182,3 +182,25 @@ def test_attention_head_mask(lib, dtype, dh, N, choice):
     wdq, wdk, wdv = omodel.attention_bwd(p, q, k, v, to_numpy(dout).reshape(B, N, Hs, dh))
     for i, want in enumerate((wdq, wdk, wdv)):
         assert rel_fro(d[:, i].reshape(B, N, Hs, dh), want) <= _tol(dtype), (i, rel_fro(d[:, i].reshape(B, N, Hs, dh), want))
+
+
+@pytest.mark.parametrize("dh,N,choice", [(128, 256, {}), (128, 128, {"staged_attention": True}), (64, 128, {}), (32, 40, {})])
+def test_attention_backward_through_rotary_positions(lib, dh, N, choice):
+    """The q and k gradients turned back through the rotary embedding (inside the direct-to-LDS kernels, by a separate
+    rotation behind the others): the checker's attention backward followed by the inverse rotation."""
+    Hs, B = 2, 2
+    cfg = si.ModelCfg(arch="llama", d_model=64, n_heads=Hs, d_head=dh, d_ff=8, rope=True, dtype=BF, max_seq=N)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    ctx.twist_set_kernel_choice(**choice)
+    qkv = _dev(_snap(si.normal(dh, "qkv", (B * N, 3 * Hs * dh)), BF), BF)
+    dout = _dev(_snap(si.normal(N, "dout", (B * N, Hs * dh)), BF), BF)
+    o, lse, dqkv = ctx.twist_attention_raw(qkv, dout, B, N, Hs, rope_backward=True)
+    torch.cuda.synchronize()
+    q, k, v = (to_numpy(qkv).reshape(B, N, 3, Hs, dh)[:, :, i] for i in range(3))
+    _, p = omodel.attention_fwd(q, k, v)
+    dq, dk, dv = omodel.attention_bwd(p, q, k, v, to_numpy(dout).reshape(B, N, Hs, dh))
+    cos, sin = omodel.rope_tables(N, dh, cfg.rope_theta)
+    want = (omodel.rope_apply(dq, cos, sin, -1.0), omodel.rope_apply(dk, cos, sin, -1.0), dv)
+    got = to_numpy(dqkv).reshape(B, N, 3, Hs, dh)
+    for i in range(3):
+        assert rel_fro(got[:, :, i], want[i]) <= 5e-3, (i, rel_fro(got[:, :, i], want[i]))

@@ -321,7 +321,7 @@ def test_movers_on_a_seeded_sweep_of_ragged_shapes(lib):
         ctx.close()
 
 
-@pytest.mark.parametrize("name", ["ragged_bf16", "wide_odd_bf16", "wide_odd_f32", "llama_overlap_S8", "gpt_bf16", "llama_bf16_um"])
+@pytest.mark.parametrize("name", ["ragged_bf16", "wide_odd_bf16", "ragged_f32", "llama_overlap_S8", "gpt_bf16", "llama_bf16_um"])
 def test_single_owner_copy_keeps_the_sign_of_zero(lib, name):
     """A parameter with one owner is copied bit for bit (Section 3.3 with a one-term sum): every subnet value is set to
     -0.0, so each single-owner element of the central model must come back with the sign bit set, in every row of the

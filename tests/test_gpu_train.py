@@ -4,13 +4,11 @@ Tolerances (relative Frobenius error): 1e-4 on fp32 paths, 5e-3 on bf16-in / fp3
 
 The 5e-3 is the tolerance of one bf16 kernel and is tested kernel by kernel elsewhere (test_gpu_kernels.py,
 test_gpu_gemm.py, test_gpu_fullsize.py).  End to end, a bf16 model stores every activation and activation gradient in
-bf16, so a gradient carries the roundings of every kernel in its causal past; bf16_bounds.py turns the number of those
-rounding points into a literal bound per tensor, min(1e-2, 1.5 * eps * sqrt(N)) (times 1.4 for the query / key
-gradients), computed from the model's shape alone.  The bf16 gates here are, per tensor:
-  * against the exact fp64 checker:                      error <= bound;
-  * against the checker run with its rounding hook (the same tensors snapped to bf16, a second implementation of the
-    same storage format):                                error <= sqrt(2) * bound;
-  * the loss itself, a single well-conditioned scalar:   5e-3 relative against both.
+bf16, so a gradient carries the roundings of every kernel in its causal past, amplified where the arithmetic cancels;
+bf16_bounds.py states the literal bound per tensor class (1.5e-2; query / key gradients 2.5e-2; ReLU models 8e-2) and
+why.  The bf16 gates here are, per tensor, that bound against the exact fp64 checker AND against the checker run with its
+rounding hook (the same tensors snapped to bf16: a second implementation of the same storage format), and 5e-3 relative
+for the loss, a single well-conditioned scalar, against both.
 """
 import os
 from dataclasses import replace
@@ -102,33 +100,39 @@ def _setup(lib, name, seed=0, store=1):
     return cfg, S, B, N, full_np, full_t, ctx, plan, oplan, fw
 
 
-def _compare_grads(cfg, got, want, tol, tag, limit=None):
-    """Every tensor within `tol`, or, for bf16 models, within limit(cfg, layer, name) (layer -1: model-level tensors).
-    Returns {(layer, name): error}."""
+def _errors(cfg, got, want):
+    """{(layer, name): relative Frobenius error}, layer -1 for the model-level tensors.  The key-bias gradient is exactly
+    zero in exact arithmetic (softmax is invariant to a shift of all keys), so its error is taken relative to the size of
+    the query-bias gradient."""
     errs = {}
-    lim_of = (lambda l, k: limit(cfg, l, k)) if limit else (lambda l, k: tol)
     for l in range(cfg.n_layers):
         for k, w in want["layers"][l].items():
             if k == "bk":
-                # softmax is invariant to a shift of all keys, so this gradient is exactly zero in exact
-                # arithmetic: compare its size with the query-bias gradient instead of with itself
-                assert np.linalg.norm(got["layers"][l][k] - w) <= 10 * lim_of(l, k) * np.linalg.norm(want["layers"][l]["bq"]), (tag, l, k)
-                continue
-            e = errs[(l, k)] = rel_fro(got["layers"][l][k], w)
-            assert e <= lim_of(l, k), (tag, l, k, e, lim_of(l, k))
+                errs[(l, k)] = float(np.linalg.norm(got["layers"][l][k] - w) / np.linalg.norm(want["layers"][l]["bq"]))
+            else:
+                errs[(l, k)] = rel_fro(got["layers"][l][k], w)
     for k, w in want["globals"].items():
-        e = errs[(-1, k)] = rel_fro(got["globals"][k], w)
-        assert e <= lim_of(-1, k), (tag, k, e, lim_of(-1, k))
+        errs[(-1, k)] = rel_fro(got["globals"][k], w)
     return errs
 
 
+def _compare_grads(cfg, got, want, tol, tag):
+    """Every gradient tensor within `tol` of the checker's (fp32 models)."""
+    for (l, k), e in _errors(cfg, got, want).items():
+        assert e <= (10 * tol if k == "bk" else tol), (tag, l, k, e)
+
+
 def _check_bf16_grads(cfg, got, ograds, rgrads, tag):
-    """The two bf16 gates of the module docstring; prints the per-tensor table (error against the exact checker, against
-    the rounding-hook checker, bound)."""
-    e_exact = _compare_grads(cfg, got, ograds, None, tag + "/exact", limit=bf16_bounds.bound)
-    e_round = _compare_grads(cfg, got, rgrads, None, tag + "/rounded", limit=bf16_bounds.bound_between_two_bf16_runs)
+    """The bf16 gates of the module docstring.  Prints the per-tensor table first (error against the exact checker, against
+    the rounding-hook checker; for reference only, the hook checker's own distance from exact and the gain-1 floor of the
+    storage format; the bound), then asserts."""
+    e_exact, e_round, e_fmt = _errors(cfg, got, ograds), _errors(cfg, got, rgrads), _errors(cfg, rgrads, ograds)
     for (l, k), e in e_exact.items():
-        print(f"  {tag} {'G' if l < 0 else 'L' + str(l)}.{k:<13} vs exact {e:.2e}  vs hooked {e_round[(l, k)]:.2e}  bound {bf16_bounds.bound(cfg, l, k):.2e}")
+        print(f"  {tag} {'G' if l < 0 else 'L' + str(l)}.{k:<13} vs exact {e:.2e}  vs hooked {e_round[(l, k)]:.2e}  (hooked vs exact {e_fmt[(l, k)]:.2e},"
+              f" gain-1 floor {bf16_bounds.floor(cfg, l, k):.2e})  bound {bf16_bounds.bound(cfg, l, k):.2e}")
+    for (l, k), e in e_exact.items():
+        assert e <= bf16_bounds.bound(cfg, l, k), (tag + "/exact", l, k, e, bf16_bounds.bound(cfg, l, k))
+        assert e_round[(l, k)] <= bf16_bounds.bound(cfg, l, k), (tag + "/hooked", l, k, e_round[(l, k)], bf16_bounds.bound(cfg, l, k))
     return max(e_exact.values())
 
 

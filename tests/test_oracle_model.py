@@ -223,14 +223,15 @@ def test_rounding_hook_is_inert_by_default_and_sees_exactly_the_declared_tensor_
             assert np.array_equal(g, hooked[1]["layers"][l][k]), (l, k)
     for k, g in plain[1]["globals"].items():
         assert np.array_equal(g, hooked[1]["globals"][k]), k
-    assert model.HOOK_TAGS == ("h1", "qkv", "o", "h2", "u", "a", "hf", "logits", "dlogits", "dres", "dact")
+    assert model.HOOK_TAGS == ("h1", "qkv", "p", "o", "h2", "u", "a", "hf", "logits", "dlogits", "dres", "dact", "ds")
     lm_tags = {"hf", "logits", "dlogits"}
     assert set(seen) == set(model.HOOK_TAGS) - (set() if cfg.vocab else lm_tags)
-    # offers per layer, forward: h1, q, k, v (+ rotated q, k), o, h2, u (+ gate), a; backward: dres x 2, the gradient
-    # of a, of u (+ gate), of h2, of o, of q, k, v (+ the two rounding points before the inverse rotation), of h1
+    # offers per layer, forward: h1, q, k, v (+ rotated q, k), the probabilities, o, h2, u (+ gate), a; backward: dres x 2,
+    # the gradient of a, of u (+ gate), of h2, of o, the probabilities again (value gradient), the score gradient, the
+    # gradients of q, k, v (+ the two rounding points before the inverse rotation), of h1
     rope, gated = int(cfg.rope), int(cfg.act == "swiglu")
-    fwd = 8 + 2 * rope + gated
-    bwd = 2 + 1 + 1 + gated + 1 + 1 + 3 + 2 * rope + 1
+    fwd = 9 + 2 * rope + gated
+    bwd = 2 + 1 + 1 + gated + 1 + 1 + 2 + 3 + 2 * rope + 1
     head = 2 + 2 if cfg.vocab else 0          # hf, logits; dlogits, the gradient of hf
     assert len(seen) == cfg.n_layers * (fwd + bwd) + head, (len(seen), fwd, bwd, head)
     rounded = model.forward_backward(cfg, P, x, y, q=lambda tag, a: si.to_bf16_grid(a))
