@@ -303,6 +303,14 @@ TWIST_API twist_status twist_attention_raw(twist_ctx *ctx, const void *qkv, cons
  *                  d_pos [N, d_model] fp32 (overwritten, may be NULL) receives the sum over the batch. */
 TWIST_API twist_status twist_norm_raw(twist_ctx *ctx, const float *x, const void *w, const void *b, int32_t T, void *y, float *stats,
                                       const void *dy, float *dx, void *dxb, float *dw, float *db, float *scratch, size_t scratch_floats);
+/* twist_norm_raw for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments, results and kernels, but the scratch of the backward half is a
+ * built-in device array of 2 Mi floats (8 MiB, held on every GPU the library runs on until the process ends) instead of
+ * a caller buffer; the call allocates nothing.  TWIST_ESHAPE when ceil(T / 16) * 2 * d_model exceeds 2 Mi floats (use
+ * twist_norm_raw then).  All calls on one GPU share the array: calls that may overlap there (different streams, different
+ * contexts) race on it; calls on one stream are ordered and safe.  Nothing in the array has to start at zero. */
+TWIST_API twist_status twist_norm_raw_static(twist_ctx *ctx, const float *x, const void *w, const void *b, int32_t T, void *y, float *stats,
+                                             const void *dy, float *dx, void *dxb, float *dw, float *db);
 TWIST_API twist_status twist_rope_raw(twist_ctx *ctx, void *qkv, int32_t B, int32_t N, int32_t Hs, float sign, float *tab);
 TWIST_API twist_status twist_act_raw(twist_ctx *ctx, const void *gu, int32_t T, int32_t F, void *a, const void *da, void *dgu,
                                      const int32_t *keep, int32_t unit);

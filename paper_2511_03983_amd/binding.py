@@ -98,6 +98,7 @@ _SIGS = {
     "twist_gemm_raw": ([_vp, _i32, _i32, _i32, _i32, _vp, C.c_int64, _vp, C.c_int64, _vp, C.c_int64, _i32, C.c_float], _i32),
     "twist_attention_raw": ([_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
     "twist_norm_raw": ([_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz], _i32),
+    "twist_norm_raw_static": ([_vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp], _i32),
     "twist_rope_raw": ([_vp, _vp, _i32, _i32, _i32, C.c_float, _vp], _i32),
     "twist_act_raw": ([_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32], _i32),
     "twist_ce_raw": ([_vp, _vp, C.c_int64, _vp, _i32, _vp, _vp], _i32),
@@ -292,6 +293,11 @@ class Context:
         _check(lib.twist_norm_raw(self.h, _ptr(x), _ptr(w), _ptr(b), T, _ptr(y), _ptr(stats), _ptr(dy), _ptr(dx), _ptr(dxb), _ptr(dw), _ptr(db),
                                   _ptr(scratch), scratch.numel()), self.h)
         return y, stats, (dx, dxb, dw, db)
+
+    def twist_norm_raw_static(self, x, w, b, dy, y, stats, dx, dxb, dw, db) -> None:
+        """twist_norm_raw on caller-provided outputs with the library's built-in scratch: the call allocates nothing."""
+        _check(lib.twist_norm_raw_static(self.h, _ptr(x), _ptr(w), _ptr(b), x.shape[0], _ptr(y), _ptr(stats), _ptr(dy), _ptr(dx), _ptr(dxb),
+                                         _ptr(dw), _ptr(db)), self.h)
 
     def twist_rope_raw(self, qkv: torch.Tensor, B: int, N: int, Hs: int, sign: float = 1.0) -> None:
         """Rotary positions applied in place to the q and k heads of qkv [B*N, 3*Hs*d_head]."""

@@ -49,3 +49,42 @@ extern "C" twist_status twist_embed_raw(twist_ctx *ctx, const int32_t *tok, int3
   return twist_embed_bwd(ctx, tok, dx, d_tok, d_pos, B, N, D);
 }
 
+// ------------------------------------------------------------------------------------------------ no allocation
+// twist_norm_raw for callers that cannot allocate (code under graph capture, tight serving loops): the per-chunk partial
+// sums of the gain / bias gradients, which twist_norm_raw takes as a caller-provided scratch argument, live in a
+// file-scope device array instead.  Every GPU the library runs on holds its own copy of the array at its own address
+// until the process ends; the address is looked up once per device and kept.
+namespace {
+constexpr size_t kStaticScratchFloats = (size_t)2 << 20;  // 8 MiB: e.g. 8192 rows of 2048, or 4096 rows of 4096
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) float scratch[kStaticScratchFloats];
+float *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until first use there
+
+// The array's name is only a host-side handle: the address kernels and copies must use comes from the runtime.
+twist_status static_scratch(twist_ctx *ctx, float **out) {
+  int dev = -1;
+  TW_HIP(ctx, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) TW_FAIL(ctx, TWIST_EHIP, "twist_norm_raw_static: device ordinal %d outside [0, %d)", dev, kMaxDevices);
+  if (!g_scratch_ptr[dev]) {
+    float *p = nullptr;
+    TW_HIP(ctx, hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)));
+    if (!p) TW_FAIL(ctx, TWIST_EHIP, "twist_norm_raw_static: the runtime returned no address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TWIST_OK;
+}
+}  // namespace
+
+extern "C" twist_status twist_norm_raw_static(twist_ctx *ctx, const float *x, const void *w, const void *b, int32_t T, void *y, float *stats,
+                                              const void *dy, float *dx, void *dxb, float *dw, float *db) {
+  if (!ctx || !x || !w || !y || !stats || T < 1) TW_FAIL(ctx, TWIST_EINVAL, "twist_norm_raw_static: null argument or empty input");
+  const int D = ctx->d.d_model;
+  const size_t need = dy ? twist_norm_partial_floats(T, D) : 0;
+  if (need > kStaticScratchFloats)
+    TW_FAIL(ctx, TWIST_ESHAPE, "twist_norm_raw_static: %d rows of %d need %zu floats of scratch, the built-in array holds %zu (use twist_norm_raw)", T, D,
+            need, kStaticScratchFloats);
+  float *ptr = nullptr;
+  if (dy) TW_TRY(static_scratch(ctx, &ptr));
+  return twist_norm_raw(ctx, x, w, b, T, y, stats, dy, dx, dxb, dw, db, ptr, kStaticScratchFloats);
+}
