@@ -323,6 +323,68 @@ def bench_golden_ticket(args, tw, si, torch):
     return res
 
 
+def bench_mfma_ceiling(tw, si, torch):
+    """The bf16 matrix instruction alone on the whole chip (no loads, about half a second per setting so that the clock
+    settles where the power limit puts it): the ceiling for any kernel built on it, next to the published 2.5 PFLOP/s."""
+    ctx = tw.Context(tw.desc_from_cfg(si.CFG3))
+    out = {}
+    for wps in (1, 2, 4):
+        ctx.twist_profile_mfma_ceiling(wps, 200000)
+        out[f"{wps}_waves_per_simd_tflops"] = ctx.twist_profile_mfma_ceiling(wps, 3000000 // wps)
+    best = max(out.values())
+    out.update({"instruction": "v_mfma_f32_32x32x16_bf16, 4 independent accumulator tiles per wave", "best_tflops": best,
+                "frac_of_published_peak": best / PEAK_BF16_TFLOPS})
+    return out
+
+
+def bench_gpt2_small(args, tw, si, torch):
+    """configs[1]: GPT-2-small-shaped model (12 layers, d 768, 12 heads, d_ff 3072, vocabulary 50257, tied head), S = 4
+    subnets of 3 heads and a disjoint quarter of the neurons each, batch 8 x 1024 uniform tokens: extract, one
+    forward+backward per subnet back to back, aggregate."""
+    cfg = replace(si.CFG2, out_unit_major=True)
+    S, hs, fs, B, N = 4, 3, 768, 8, 1024
+    layers, globs = device_weights(cfg, 8, si, torch)
+    fw = tw.FullWeights(layers, globs)
+    ctx = tw.Context(tw.desc_from_cfg(cfg))
+    plan = ctx.twist_sample(S, hs, fs, seed=2)
+    nb = ctx.twist_subnet_bytes(plan, tw.STORE_GRADS)
+    stor = [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(S)]
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    toks = [torch.randint(0, cfg.vocab, (B, N + 1), generator=gen, device="cuda", dtype=torch.int32) for _ in range(S)]
+    xs, ys = [t[:, :-1].contiguous() for t in toks], [t[:, 1:].contiguous() for t in toks]
+    loss = torch.zeros(1, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    ws = None
+    t_ex, t_fb, t_ag = [], [], []
+    for it in range(2 + 5):
+        a = ev(); a.record()
+        subs = ctx.twist_extract_all(plan, fw, store=tw.STORE_GRADS, storages=stor)
+        b = ev(); b.record()
+        if ws is None:
+            ws = torch.empty(ctx.twist_workspace_bytes(subs[0], B, N), dtype=torch.uint8, device="cuda")
+        for s, sub in enumerate(subs):
+            ctx.twist_subnet_fwd_bwd(sub, xs[s], ys[s], ws, loss)
+        c = ev(); c.record()
+        ctx.twist_aggregate(plan, subs, fw)
+        d = ev(); d.record(); torch.cuda.synchronize()
+        if it >= 2:
+            t_ex.append(a.elapsed_time(b)); t_fb.append(b.elapsed_time(c)); t_ag.append(c.elapsed_time(d))
+        for sub in subs:
+            sub.close()
+    med = lambda v: sorted(v)[len(v) // 2]
+    fl = flops_fwd_bwd(cfg, hs, fs, B, N)
+    fb = med(t_fb) / S
+    res = {"extract_all_ms": med(t_ex), "fwd_bwd_x4_ms": med(t_fb), "aggregate_ms": med(t_ag), "fwd_bwd_ms_per_subnet": fb,
+           "fwd_bwd_tokens_per_s": B * N / (fb * 1e-3), "fwd_bwd_tflops": fl / (fb * 1e-3) / 1e12,
+           "fwd_bwd_frac_mfma_peak": fl / (fb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "whole_pass_tokens_per_s": S * B * N / ((med(t_ex) + med(t_fb) + med(t_ag)) * 1e-3), "loss": loss.item(),
+           "workload": "configs[1]: S=4 disjoint quarter-width subnets (3 of 12 heads, 768 of 3072 neurons), batch 8x1024, tied 50257-token head"}
+    plan.close()
+    del stor, ws, layers, globs, fw
+    torch.cuda.empty_cache()
+    return res
+
+
 def bench_clock_under_load(tw, si, torch):
     """Shader clock reported by rocm-smi while the projection kernel runs back to back on the whole chip (8192^3, about
     3 s), next to the idle reading: the published MFMA peak assumes the 2.4 GHz boost clock, the chip holds less under
@@ -452,6 +514,30 @@ def cpu_baseline(si):
                       f"({times[1]:.2f} s, {times[2]:.2f} s) and extrapolated to 22 layers"}
 
 
+def cpu_baseline_one_thread(si):
+    """The same checker held to ONE thread, on a smaller bounded sample (1 x 256 tokens, 1 and 2 layers at the
+    Llama-1B-shaped half-width subnet's widths and vocabulary), extrapolated to 22 layers the same way."""
+    from oracle import model as omodel, move as omove
+    from oracle.sample import sample_plan
+    from threadpoolctl import threadpool_limits
+    B, N = 1, 256
+    times = {}
+    with threadpool_limits(limits=1):
+        for L in (1, 2):
+            cfg = replace(si.CFG3, n_layers=L)
+            full = si.make_weights(cfg, 0)
+            plan = sample_plan(L, cfg.n_heads, cfg.n_ffn_units, 4, 8, 2816, 0)
+            sub = omove.extract(full, plan, 0, cfg.d_head)
+            t = si.tokens_zipf(cfg.vocab, B, N, 5)
+            t0 = time.perf_counter()
+            omodel.forward_backward(cfg, sub, t[:, :-1], t[:, 1:])
+            times[L] = time.perf_counter() - t0
+    per_layer = max(times[2] - times[1], 1e-9)
+    return {"value": B * N / (times[1] + 21 * per_layer), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"fp64 numpy checker on one thread, forward+backward of the Llama-1B-shaped half-width subnet on {B}x{N} tokens, measured with 1 "
+                      f"and 2 layers ({times[1]:.2f} s, {times[2]:.2f} s) and extrapolated to 22 layers"}
+
+
 def cpu_baseline_movers(si):
     """The CPU checker's extract and aggregate on a bounded sample of the mover workload: ONE Llama-7B-shaped layer at a
     quarter of its width (d_model 4096, 8 of 32 heads, d_ff 2752 of 11008: same row lengths, a quarter of the rows),
@@ -490,7 +576,8 @@ def main():
     ap.add_argument("--skip-golden", action="store_true", help="skip the pruned-versus-unpruned 7B-shaped forward+backward leg")
     ap.add_argument("--native-round", action="store_true", help="also time the same round through twist_round (library-side loop, one subnet resident)")
     ap.add_argument("--skip-clock", action="store_true", help="skip the rocm-smi clock reading under projection load")
-    ap.add_argument("--ablation", action="store_true", help="also run the GPT-2-small-shaped latency study (kept blocks 10/8/6/4 of 12)")
+    ap.add_argument("--skip-ablation", action="store_true", help="skip the GPT-2-small-shaped latency study (kept blocks 10/8/6/4 of 12)")
+    ap.add_argument("--skip-gpt2", action="store_true", help="skip the GPT-2-small-shaped leg (4 x forward+backward at 8 x 1024, then aggregate)")
     ap.add_argument("--no-overlap", action="store_true", help="keep every kernel on one stream also in the timed region (for per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -517,7 +604,11 @@ def main():
         any(k.startswith("ROCPROF") for k in os.environ)
     clock = None if (args.skip_movers or args.skip_clock or profiled) else bench_clock_under_load(tw, si, torch)
     log("[bench] clock under projection load:", json.dumps(clock))
-    ablation = bench_latency_ablation(args, tw, si, torch) if args.ablation else None
+    gpt2 = None if args.skip_gpt2 else bench_gpt2_small(args, tw, si, torch)
+    log("[bench] GPT-2-small-shaped leg:", json.dumps(gpt2))
+    ceiling = None if (args.skip_clock or profiled) else bench_mfma_ceiling(tw, si, torch)
+    log("[bench] matrix-instruction ceiling:", json.dumps(ceiling))
+    ablation = None if args.skip_ablation else bench_latency_ablation(args, tw, si, torch)
     if ablation:
         log("[bench] latency ablation (GPT-2-small shape):", json.dumps(ablation))
     cpu = None if args.skip_cpu else cpu_baseline(si)
@@ -569,6 +660,16 @@ def main():
         out["clock_under_projection_load"] = clock
     if golden:
         out["golden_ticket_llama7b_fwd_bwd"] = golden
+    if gpt2:
+        out["gpt2_small_4_subnets"] = gpt2
+    if ceiling:
+        out["mfma_only_ceiling"] = ceiling
+    if cpu and not args.skip_cpu:
+        try:
+            out["cpu_baseline_one_thread"] = cpu_baseline_one_thread(si)
+            log("[bench] cpu baseline (one thread):", json.dumps(out["cpu_baseline_one_thread"]))
+        except ImportError:
+            pass
     if ablation:
         out["latency_ablation_gpt2_small"] = ablation
     print(json.dumps(out), flush=True)

@@ -531,6 +531,29 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int
   }
 }
 
+// Measurement aid: nothing but the projection kernels' matrix instruction, four independent accumulator tiles per wave
+// (enough to issue back to back), operands in registers, no loads; the result is stored so that the loop stays.
+__global__ __launch_bounds__(256) void mfma_only_kernel(int iters, float *sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7)); b[i] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7)); }
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += acc[j][r];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+}
+
 // number of k parts for a product with few 256x256 output tiles and a long k (1 = do not split)
 int choose_ksplit(int M, int N, int K, int *kchunk) {
   const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
@@ -653,6 +676,32 @@ extern "C" twist_status twist_set_kernel_choice(twist_ctx *ctx, int32_t gemm_til
   ctx->gemm_tile = gemm_tile;
   ctx->plain_only = plain_only != 0;
   ctx->staged_attention = staged_attention != 0;
+  return TWIST_OK;
+}
+
+extern "C" twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves_per_simd, int32_t iters, float *sink, size_t sink_floats, double *tflops) {
+  if (!ctx || !sink || !tflops) TW_FAIL(ctx, TWIST_EINVAL, "twist_profile_mfma_ceiling: null argument");
+  if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) TW_FAIL(ctx, TWIST_EINVAL, "twist_profile_mfma_ceiling: waves_per_simd in [1, 8], iters >= 1");
+  hipDeviceProp_t prop;
+  int dev = 0;
+  TW_HIP(ctx, hipGetDevice(&dev));
+  TW_HIP(ctx, hipGetDeviceProperties(&prop, dev));
+  const int blocks = prop.multiProcessorCount * waves_per_simd;  // a workgroup is 4 waves, one per SIMD of a compute unit
+  if (sink_floats < (size_t)blocks * 256) TW_FAIL(ctx, TWIST_ESHAPE, "twist_profile_mfma_ceiling: sink needs %zu floats", (size_t)blocks * 256);
+  hipEvent_t e0, e1;
+  TW_HIP(ctx, hipEventCreate(&e0));
+  TW_HIP(ctx, hipEventCreate(&e1));
+  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters / 8 + 1, sink);  // warm-up
+  (void)hipEventRecord(e0, ctx->stream);
+  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters, sink);
+  (void)hipEventRecord(e1, ctx->stream);
+  hipError_t err = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  TW_HIP(ctx, err);
+  *tflops = (double)blocks * 4.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16) / ((double)ms * 1e-3) / 1e12;
   return TWIST_OK;
 }
 

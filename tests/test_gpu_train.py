@@ -702,3 +702,43 @@ def test_masked_full_model_equals_the_extracted_subnet(lib, name):
             _compare_grads(cfg, cut, ograds, tol, name + "/masked")
     with pytest.raises(lib.TwistError):      # a partial subnet cannot stand in for the full model
         ctx.twist_subnet_fwd_bwd_masked(ctx.twist_extract(plan, fw, 0, store=lib.STORE_GRADS), plan, 0, x, y, ws, loss)
+
+
+def test_train_x_eval_y_grid_matches_checker(lib):
+    """Section 5.1 ("Architectural Robustness"): a model trained for one round with subnets of X of 12 blocks (heads and
+    FFN blocks alike, first and last layer shared) is evaluated, without retraining, through deployment subnets of Y of
+    12 blocks, for X, Y in {12, 10, 8, 6, 4}; every entry of the grid of evaluation losses against the checker's loop."""
+    from paper_2511_03983_amd import harness
+    cfg = si.ModelCfg(n_layers=3, d_model=48, n_heads=12, d_head=4, d_ff=96, ffn_granule=8, vocab=61, max_seq=16)
+    S, steps, B, N, lr, seed, eval_seed = 3, 2, 2, 16, 5e-2, 5, 77
+    shared = [1, 0, 1]
+    ks = (12, 10, 8, 6, 4)
+    full_np = si.make_weights(cfg, 9, std=0.1, generic=True)
+    full_t = to_device(full_np, cfg)
+    ctx = lib.Context(lib.desc_from_cfg(cfg))
+    batches = {X: [[_data(cfg, B, N, 100 * X + 10 * s + j) for j in range(steps)] for s in range(S)] for X in ks}
+    ev = _data(cfg, B, N, 999)
+
+    def train_batches(X, r):
+        rows = batches[X]
+        return (torch.stack([torch.stack([b[2] for b in row]) for row in rows]), torch.stack([torch.stack([b[3] for b in row]) for row in rows]))
+
+    grid = harness.robustness_grid(ctx, full_t["layers"], full_t["globals"], train_batches, (ev[2], ev[3]), 12, ks, ks, S=S, rounds=1,
+                                   opt={"kind": lib.OPT_SGD, "lr": lr}, seed=seed, layer_shared=shared, eval_seed=eval_seed)
+    for X in ks:
+        oplan = sample_plan(cfg.n_layers, 12, 12, S, X, X, seed, 0, layer_shared=shared)
+        osubs = []
+        for s in range(S):
+            osub = omove.extract(full_np, oplan, s, cfg.d_head, cfg.ffn_granule)
+            for j in range(steps):
+                _, og = omodel.forward_backward(cfg, osub, batches[X][s][j][0], batches[X][s][j][1])
+                ooptim.sgd_step(osub, {"layers": og["layers"], "globals": og["globals"]}, lr)
+            osubs.append(osub)
+        central = omove.aggregate(full_np, oplan, osubs, cfg.d_head, cfg.ffn_granule)
+        for Y in ks:
+            eplan = sample_plan(cfg.n_layers, 12, 12, 1, Y, Y, eval_seed, 0, layer_shared=shared, require_coverage=False)
+            want = omodel.forward_loss(cfg, omove.extract(central, eplan, 0, cfg.d_head, cfg.ffn_granule), ev[0], ev[1])
+            assert abs(grid[X][Y] - want) <= 1e-4 * abs(want), (X, Y, grid[X][Y], want)
+    # training at different widths left different models behind, and the central model was restored afterwards
+    assert len({round(grid[X][12], 5) for X in ks}) > 1
+    assert np.array_equal(to_numpy(full_t["layers"][1]["wq"]), np.asarray(full_np["layers"][1]["wq"], np.float32).astype(np.float64))
