@@ -328,10 +328,12 @@ TWIST_API twist_status twist_profile_gemm_read(twist_ctx *ctx, int64_t *launches
 /* Measurement aid: the rate of the projection kernels' matrix instruction alone (v_mfma_f32_32x32x16_bf16, operands in
  * registers, no loads, four independent accumulator tiles per wave), with `waves_per_simd` waves on every SIMD of the
  * chip for `iters` iterations of four instructions: the ceiling any kernel built on that instruction has on this chip at
- * the clock it holds under that load.  sink (dev, at least compute units * waves_per_simd * 256 floats) receives the
- * accumulators.  Synchronises the ctx's stream; *tflops (host) receives the rate. */
-TWIST_API twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves_per_simd, int32_t iters, float *sink, size_t sink_floats,
-                                                  double *tflops);
+ * the clock it holds under that load.  random_operands = 0 feeds small constants, 1 pseudo-random values of magnitude
+ * about one (the chip's power limit, hence its clock, depends on how many operand bits toggle).  sink (dev, at least
+ * compute units * waves_per_simd * 256 floats) receives the accumulators.  Synchronises the ctx's stream; *tflops
+ * (host) receives the rate. */
+TWIST_API twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves_per_simd, int32_t iters, int32_t random_operands, float *sink,
+                                                  size_t sink_floats, double *tflops);
 
 /* The weight-gradient projections of twist_subnet_fwd_bwd run on a second stream that the library creates
  * (default priority), next to the input-gradient kernels on the context's stream; the call still returns with

@@ -106,7 +106,7 @@ _SIGS = {
     "twist_set_kernel_choice": ([_vp, _i32, _i32, _i32], _i32),
     "twist_profile_gemm": ([_vp, _i32], _i32),
     "twist_set_overlap": ([_vp, _i32], _i32),
-    "twist_profile_mfma_ceiling": ([_vp, _i32, _i32, _vp, _sz, C.POINTER(C.c_double)], _i32),
+    "twist_profile_mfma_ceiling": ([_vp, _i32, _i32, _i32, _vp, _sz, C.POINTER(C.c_double)], _i32),
     "twist_profile_gemm_read": ([_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)], _i32),
 }
 for _name, (_args, _res) in _SIGS.items():
@@ -337,11 +337,11 @@ class Context:
     def twist_set_overlap(self, enable: bool) -> None:
         _check(lib.twist_set_overlap(self.h, int(enable)), self.h)
 
-    def twist_profile_mfma_ceiling(self, waves_per_simd: int = 2, iters: int = 20000) -> float:
+    def twist_profile_mfma_ceiling(self, waves_per_simd: int = 2, iters: int = 20000, random_operands: bool = True) -> float:
         """TFLOP/s of the bf16 matrix instruction alone on the whole chip (no loads)."""
         sink = torch.empty(1024 * 8 * 256, dtype=torch.float32, device="cuda")
         tf = C.c_double()
-        _check(lib.twist_profile_mfma_ceiling(self.h, waves_per_simd, iters, _ptr(sink), sink.numel(), C.byref(tf)), self.h)
+        _check(lib.twist_profile_mfma_ceiling(self.h, waves_per_simd, iters, int(random_operands), _ptr(sink), sink.numel(), C.byref(tf)), self.h)
         return tf.value
 
     def twist_profile_gemm(self, enable: bool) -> None:

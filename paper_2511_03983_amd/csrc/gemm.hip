@@ -533,18 +533,34 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *ws, int
 
 // Measurement aid: nothing but the projection kernels' matrix instruction, four independent accumulator tiles per wave
 // (enough to issue back to back), operands in registers, no loads; the result is stored so that the loop stays.
-__global__ __launch_bounds__(256) void mfma_only_kernel(int iters, float *sink) {
-  bf16x8 a, b;
+// random_operands = 0: small constants (few bits toggle between instructions); 1: four different operand pairs of
+// pseudo-random bf16 values of magnitude ~1 in rotation, which is what the multipliers see in a real projection and
+// what the chip's power limit responds to.
+__global__ __launch_bounds__(256) void mfma_only_kernel(int iters, float *sink, int random_operands) {
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7)); b[i] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7)); }
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint32_t h = (threadIdx.x * 8u + i + 977u * j + 131071u * blockIdx.x) * 2654435761u;
+      h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+      // sign and 7 mantissa bits at random, exponent in {2^-2 .. 2^1}: a spread like that of normalised activations
+      const uint16_t ra = (uint16_t)(((h & 0x8000u)) | ((125u + ((h >> 7) & 3u)) << 7) | (h & 0x7fu));
+      const uint16_t rb = (uint16_t)((((h >> 16) & 0x8000u)) | ((125u + ((h >> 23) & 3u)) << 7) | ((h >> 16) & 0x7fu));
+      const uint16_t ca = (uint16_t)(0x3a80u + ((threadIdx.x + i) & 7)), cb = (uint16_t)(0x3b00u + ((threadIdx.x * 3 + i) & 7));
+      a[j][i] = __builtin_bit_cast(__bf16, random_operands ? ra : ca);
+      b[j][i] = __builtin_bit_cast(__bf16, random_operands ? rb : cb);
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-  for (int it = 0; it < iters; ++it) {
+  for (int it = 0; it < iters; it += 4) {  // four iterations per trip so that the operand rotation is static
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + r) & 3], acc[j], 0, 0, 0);
   }
   float t = 0.f;
 #pragma unroll
@@ -679,7 +695,8 @@ extern "C" twist_status twist_set_kernel_choice(twist_ctx *ctx, int32_t gemm_til
   return TWIST_OK;
 }
 
-extern "C" twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves_per_simd, int32_t iters, float *sink, size_t sink_floats, double *tflops) {
+extern "C" twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves_per_simd, int32_t iters, int32_t random_operands, float *sink,
+                                                   size_t sink_floats, double *tflops) {
   if (!ctx || !sink || !tflops) TW_FAIL(ctx, TWIST_EINVAL, "twist_profile_mfma_ceiling: null argument");
   if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) TW_FAIL(ctx, TWIST_EINVAL, "twist_profile_mfma_ceiling: waves_per_simd in [1, 8], iters >= 1");
   hipDeviceProp_t prop;
@@ -691,9 +708,9 @@ extern "C" twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves
   hipEvent_t e0, e1;
   TW_HIP(ctx, hipEventCreate(&e0));
   TW_HIP(ctx, hipEventCreate(&e1));
-  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters / 8 + 1, sink);  // warm-up
+  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters / 8 + 1, sink, random_operands);  // warm-up
   (void)hipEventRecord(e0, ctx->stream);
-  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters, sink);
+  hipLaunchKernelGGL(mfma_only_kernel, dim3(blocks), dim3(256), 0, ctx->stream, iters, sink, random_operands);
   (void)hipEventRecord(e1, ctx->stream);
   hipError_t err = hipEventSynchronize(e1);
   float ms = 0.f;
@@ -701,7 +718,8 @@ extern "C" twist_status twist_profile_mfma_ceiling(twist_ctx *ctx, int32_t waves
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   TW_HIP(ctx, err);
-  *tflops = (double)blocks * 4.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16) / ((double)ms * 1e-3) / 1e12;
+  const double trips = (double)((iters + 3) / 4);  // the kernel runs four iterations per trip
+  *tflops = (double)blocks * 4.0 * trips * 16.0 * (2.0 * 32 * 32 * 16) / ((double)ms * 1e-3) / 1e12;
   return TWIST_OK;
 }
 

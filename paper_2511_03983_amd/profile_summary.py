@@ -1,10 +1,14 @@
 """Condense rocprofv3 output of a run of this library into the short text summaries kept under profiles/.
 
     python -m paper_2511_03983_amd.profile_summary stats <x_kernel_stats.csv> <out.txt> "<command that was profiled>"
+    python -m paper_2511_03983_amd.profile_summary trace <x_kernel_trace.csv> <out.txt> "<command that was profiled>"
     python -m paper_2511_03983_amd.profile_summary pmc   <x_counter_collection.csv> <out.txt> "<command that was profiled>"
     python -m paper_2511_03983_amd.profile_summary mfma  <x_counter_collection.csv> <out.txt> "<command that was profiled>"
 
-`stats` takes the per-kernel table of `rocprofv3 --kernel-trace --stats --output-format csv`; `pmc` takes the
+`stats` takes the per-kernel table of `rocprofv3 --kernel-trace --stats --output-format csv`; `trace` takes the
+per-dispatch table of the same run and gives one row per (kernel, grid size), so that launches of one kernel on
+different shapes or layouts (the movers in the two storage layouts, each projection shape) keep their own durations;
+`pmc` takes the
 per-dispatch counter table of `rocprofv3 --pmc <counter> --output-format csv`, sums the rows of each dispatch and
 averages per (kernel, grid size); `mfma` takes a run with SQ_VALU_MFMA_BUSY_CYCLES, SQ_BUSY_CYCLES and
 SQ_INSTS_VALU_MFMA_MOPS_BF16 and prints one row per kernel with the matrix-pipe utilisation derived from them.
@@ -37,6 +41,28 @@ def stats(src: str, out: str, cmd: str) -> None:
                 continue
             f.write(f"{short(r['Name']):78s} {int(r['Calls']):7d} {float(r['TotalDurationNs']) / 1e3:12.1f} "
                     f"{float(r['AverageNs']) / 1e3:10.2f} {pct:6.2f}\n")
+
+
+def trace(src: str, out: str, cmd: str) -> None:
+    agg = collections.defaultdict(lambda: [0, 0.0, float("inf"), 0.0])
+    with open(src, newline="") as f:
+        for r in csv.DictReader(f):
+            dur = (float(r["End_Timestamp"]) - float(r["Start_Timestamp"])) / 1e3
+            grid = "x".join(str(r.get(k, "")) for k in ("Grid_Size_X", "Grid_Size_Y", "Grid_Size_Z")) if "Grid_Size_X" in r else str(r.get("Grid_Size", ""))
+            a = agg[(short(r["Kernel_Name"]), grid)]
+            a[0] += 1
+            a[1] += dur
+            a[2] = min(a[2], dur)
+            a[3] = max(a[3], dur)
+    total = sum(a[1] for a in agg.values())
+    with open(out, "w") as f:
+        f.write("# rocprofv3 --kernel-trace summary per (kernel, grid size in threads): durations in microseconds\n# command: %s\n" % cmd)
+        f.write("# 'other:' rows (the benchmark's own weight generation / perturbation kernels) and rows under 0.02 % of the total are left out\n")
+        f.write(f"{'kernel':72s} {'grid':>14s} {'calls':>7s} {'total_us':>12s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'%':>6s}\n")
+        for (kn, grid), (n, tot, lo, hi) in sorted(agg.items(), key=lambda x: -x[1][1]):
+            if kn.startswith("other:") or tot < 2e-4 * total:
+                continue
+            f.write(f"{kn[:72]:72s} {grid:>14s} {n:7d} {tot:12.1f} {tot / n:10.2f} {lo:10.2f} {hi:10.2f} {100.0 * tot / total:6.2f}\n")
 
 
 def pmc(src: str, out: str, cmd: str) -> None:
@@ -89,7 +115,7 @@ def mfma(src: str, out: str, cmd: str) -> None:
 
 
 if __name__ == "__main__":
-    modes = {"stats": stats, "pmc": pmc, "mfma": mfma}
+    modes = {"stats": stats, "trace": trace, "pmc": pmc, "mfma": mfma}
     if len(sys.argv) != 5 or sys.argv[1] not in modes:
         sys.exit(__doc__)
     modes[sys.argv[1]](sys.argv[2], sys.argv[3], sys.argv[4])
