@@ -248,7 +248,15 @@ twist_status twist_train_fwd_bwd(twist_ctx *ctx, twist_subnet *sub, const void *
     if (forward_only) return TWIST_OK;
     // projection weight gradient, then the gradient flowing back into the final norm
     TW_TRY(gemm(GEMM_TN, V, D, T, w.logits, w.ld_logits, w.hf, D, G(wout), D, 1));
-    TW_TRY(gemm(GEMM_NN, T, D, V, w.logits, w.ld_logits, P(wout), D, w.dh, D, 0));
+    {
+      // gradient of the final normed input: few output tiles ([T, d_model]) and a contraction as long as the vocabulary, so
+      // it may be cut along the vocabulary like the weight gradients (the scratch is free here: the second stream's
+      // projections of this pass have not started, those of the previous pass were joined before it returned)
+      GemmEpilogue e;
+      e.out = w.dh; e.out_f32 = 0;
+      e.splitk_ws = w.splitk; e.splitk_floats = kSplitkFloats;
+      TW_TRY(twist_gemm(ctx, bf, GEMM_NN, T, D, V, w.logits, w.ld_logits, P(wout), D, D, e));
+    }
     TW_TRY(norm_bwd(2 * d.n_layers, w.dh, x_last, P(L.global[TWIST_FINAL_NORM_W]), 0, w.dxb, G(L.global[TWIST_FINAL_NORM_W]),
                     G(L.global[TWIST_FINAL_NORM_B])));
   } else {
