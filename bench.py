@@ -61,9 +61,9 @@ def flops_fwd_bwd(cfg, hs, F, B, N):
 # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this benchmark's own command and
 # calibrated against streaming kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; the counter
 # sits behind the L2, so reads served by the Infinity Cache are included).  Source: profiles/bench_hbm_traffic_fetch_write.txt
-TRAFFIC_PROJECTION_LAUNCH = 316.6e6         # average over every projection launch of a forward+backward pass
-TRAFFIC_EXTRACT_LAYER_LAUNCH = 405.3e6      # one layer of one subnet at the 7B shape, unit-major layout
-TRAFFIC_AGGREGATE_LAYER_LAUNCH = 2029.7e6   # one layer, 8 subnets
+TRAFFIC_PROJECTION_LAUNCH = 316.7e6         # average over every projection launch of a forward+backward pass
+TRAFFIC_EXTRACT_LAYER_LAUNCH = 405.2e6      # one layer of one subnet at the 7B shape, unit-major layout
+TRAFFIC_AGGREGATE_LAYER_LAUNCH = 2029.6e6   # one layer, 8 subnets
 
 
 def bytes_fwd_bwd_projections(cfg, hs, F, B, N):

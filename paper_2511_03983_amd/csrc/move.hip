@@ -814,14 +814,14 @@ __global__ __launch_bounds__(kThreads) void to_f32_kernel(const void *src, float
     dst[i] = elem_to_f32<ES>(reinterpret_cast<const E *>(src)[i]);
 }
 
-// bf16 -> fp32, eight values per thread and step: one 16-byte load, two 16-byte stores (a bf16 value is the upper half of
-// the fp32 value with the same bits)
-__global__ __launch_bounds__(kThreads) void bf16_to_f32_vec_kernel(const u32x4 *src, u32x4 *dst, int64_t n_vec) {
+// bf16 -> fp32, four values per thread and step: one 8-byte load, one 16-byte store, so that a wave's store instruction
+// writes 1 KB of consecutive bytes (a bf16 value is the upper half of the fp32 value with the same bits)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__global__ __launch_bounds__(kThreads) void bf16_to_f32_vec_kernel(const u32x2 *src, u32x4 *dst, int64_t n_vec) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += stride) {
-    const u32x4 u = __builtin_nontemporal_load(src + i);
-    __builtin_nontemporal_store(u32x4{u.x << 16, u.x & 0xffff0000u, u.y << 16, u.y & 0xffff0000u}, dst + 2 * i);
-    __builtin_nontemporal_store(u32x4{u.z << 16, u.z & 0xffff0000u, u.w << 16, u.w & 0xffff0000u}, dst + 2 * i + 1);
+    const u32x2 u = __builtin_nontemporal_load(src + i);
+    __builtin_nontemporal_store(u32x4{u.x << 16, u.x & 0xffff0000u, u.y << 16, u.y & 0xffff0000u}, dst + i);
   }
 }
 
@@ -883,9 +883,9 @@ twist_status twist_launch_accumulate(twist_ctx *ctx, const MoveLaunch &ml, int t
 twist_status twist_launch_to_f32(twist_ctx *ctx, const void *src, float *dst, int64_t n) {
   if (n <= 0) return TWIST_OK;
   if (ctx->esize() == 2 && n % 8 == 0 && (reinterpret_cast<uintptr_t>(src) % 16) == 0 && (reinterpret_cast<uintptr_t>(dst) % 16) == 0) {
-    const int64_t nv = n / 8;
+    const int64_t nv = n / 4;
     const int vblocks = (int)std::min<int64_t>((nv + kThreads - 1) / kThreads, 256 * 16);
-    hipLaunchKernelGGL(bf16_to_f32_vec_kernel, dim3(vblocks), dim3(kThreads), 0, ctx->stream, static_cast<const u32x4 *>(src), reinterpret_cast<u32x4 *>(dst), nv);
+    hipLaunchKernelGGL(bf16_to_f32_vec_kernel, dim3(vblocks), dim3(kThreads), 0, ctx->stream, static_cast<const u32x2 *>(src), reinterpret_cast<u32x4 *>(dst), nv);
     TW_HIP(ctx, hipGetLastError());
     return TWIST_OK;
   }
