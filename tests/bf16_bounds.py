@@ -26,7 +26,8 @@ Bounds held by the tests, per tensor class, against the exact checker and agains
   loss (a well-conditioned scalar)                                  5e-3 relative
   ReLU models, any gradient                                         8e-2
   query / key weights and biases (wq, wk, bq; bk relative to bq)    2.5e-2
-  every other gradient                                              1.5e-2
+  every other gradient, d_model >= 4096                             1.5e-2
+  every other gradient                                              1e-2
 What keeps a percent-level error on one path from hiding under these: the per-kernel 5e-3 tests above, the same
 models in fp32 end to end at 1e-4 (same orchestration, same kernels where they are not bf16-specific), and the
 bit-exact comparisons between kernel families and schedules.
@@ -75,4 +76,6 @@ def floor(cfg, layer, name):
 def bound(cfg, layer, name):
     if cfg.act == "relu":
         return 8e-2
-    return 2.5e-2 if name in QK else 1.5e-2
+    if name in QK:
+        return 2.5e-2
+    return 1.5e-2 if cfg.d_model >= 4096 else 1e-2
