@@ -728,138 +728,169 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     }
 }
 
-__global__ __launch_bounds__(256) void flash_bwd_dkv_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
+// dK / dV with 8 waves per workgroup, one workgroup per CU.  The waves w and w + 4 of a SIMD own the SAME 32 keys and
+// split the work of a query tile between them instead of each doing all of it with one wave per SIMD:
+//   producer (w < 4): S = Q K^T and dP = dO V^T for 32 queries x its 32 keys (K and V fragments stay in registers),
+//                     then P = 2^(S sc - lse) and dS = P (dP - delta) scale, handed over through LDS in exactly the
+//                     register layout the next products take them in (lane to same lane, 64 bytes per lane);
+//   consumer (w >= 4): dV^T += dO^T P and dK^T += Q^T dS for the 32 queries the producer finished one phase earlier
+//                     (all 128 accumulator registers are here, the producer has none).
+// Both issue 16 matrix instructions per phase of 32 queries; the producer's exponentials run under the consumer's
+// products on the same SIMD.  One workgroup barrier per phase.  The 64-query Q / dO tiles live in three LDS stages (the
+// tile being loaded, the producer's, and the consumer's, which is half a tile behind), the hand-over area in two.
+// A workgroup handles the key blocks p and nkb-1-p one after the other, so that all workgroups carry the same work.
+constexpr int DKV_LD_OFF = 3 * STAGE_B;             // per stage: 64 log-sum-exps, 64 deltas
+constexpr int DKV_XCH_OFF = DKV_LD_OFF + 3 * 512;   // [2 phases][4 key blocks][P lo, P hi, dS lo, dS hi][64 lanes] x 16 bytes
+constexpr int DKV_SMEM = DKV_XCH_OFF + 2 * 4 * 4096;
+#define DL_WAIT_LGKM0 __builtin_amdgcn_s_waitcnt(0xc07f)
+
+__global__ __launch_bounds__(512) void flash_bwd_dkv_dl_kernel(const uint16_t *qkv, const uint16_t *dout, const float *lse, const float *delta,
                                                                uint16_t *dqkv, int N, int Hs, float scale, const float *rope, const int32_t *keep) {
-  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 2 * 512];  // + per stage: 64 log-sum-exps, 64 deltas
-  const int nkb = N / 128, nbh = gridDim.x / nkb;
-  const int rank = snake_rank(blockIdx.x, gridDim.x);
-  const int kb = rank / nbh;
-  const int bh = rank % nbh, b = bh / Hs, h = bh % Hs;
+  __shared__ __attribute__((aligned(1024))) char smem[DKV_SMEM];
+  const int nkb = N / 128, npair = (nkb + 1) / 2, nbh = gridDim.x / npair;
+  const int pr = (int)blockIdx.x / nbh;
+  const int bh = blockIdx.x % nbh, b = bh / Hs, h = bh % Hs;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+  const int wk = wave & 3;
+  const bool producer = wave < 4;
   const int64_t HD = (int64_t)Hs * DH, ld = 3 * HD;
   const uint16_t *batch = qkv + (int64_t)b * N * ld;
   const uint16_t *qp = batch + (int64_t)h * DH;
   const uint16_t *gbatch = dout + (int64_t)b * N * HD;
-  const int k0 = kb * 128 + wave * 32, kv = k0 + c;
   const float sc = scale * kLog2e;
   const float *lse_b = lse + ((int64_t)b * Hs + h) * N, *del_b = delta + ((int64_t)b * Hs + h) * N;
   const desc_t rq = make_desc(batch, (uint32_t)(N * ld * 2)), rg = make_desc(gbatch, (uint32_t)(N * HD * 2));
   const desc_t rl = make_desc(lse_b, (uint32_t)(N * 4)), rd = make_desc(del_b, (uint32_t)(N * 4));
   const uint32_t qstep = (uint32_t)(64 * ld * 2), gstep = (uint32_t)(64 * HD * 2);
-  TileLoader lq, lg;
-  lq.init(ld, (uint32_t)(h * DH * 2), wave, lane);
-  lg.init(HD, (uint32_t)(h * DH * 2), wave, lane);
+  TileLoader lt;  // the producers bring in the query tile and the log-sum-exps, the consumers the dO tile and the deltas
+  if (producer) lt.init(ld, (uint32_t)(h * DH * 2), wk, lane);
+  else lt.init(HD, (uint32_t)(h * DH * 2), wk, lane);
   ReadOffsets ro;
   ro.init(lane);
   const bool masked = keep && keep[h] < 0;  // masked head: the gradients are zero, nothing is loaded
-  const int qt0 = kb * 2, n_q = masked ? qt0 : N / 64;
   auto issue = [&](int qt, int st) {
-    lq.issue(rq, smem + st * STAGE_B, (uint32_t)qt * qstep, wave);
-    lg.issue(rg, smem + st * STAGE_B + TILE_B, (uint32_t)qt * gstep, wave);
-    // the tile's 64 log-sum-exps and deltas: one 4-byte-per-lane load each, by waves 0 and 1
-    if (wave == 0) dma<4>(rl, smem + 2 * STAGE_B + st * 512, (uint32_t)((qt * 64 + lane) * 4));
-    if (wave == 1) dma<4>(rd, smem + 2 * STAGE_B + st * 512 + 256, (uint32_t)((qt * 64 + lane) * 4));
+    if (producer) {
+      lt.issue(rq, smem + st * STAGE_B, (uint32_t)qt * qstep, wk);
+      if (wk == 0) dma<4>(rl, smem + DKV_LD_OFF + st * 512, (uint32_t)((qt * 64 + lane) * 4));
+    } else {
+      lt.issue(rg, smem + st * STAGE_B + TILE_B, (uint32_t)qt * gstep, wk);
+      if (wk == 0) dma<4>(rd, smem + DKV_LD_OFF + st * 512 + 256, (uint32_t)((qt * 64 + lane) * 4));
+    }
   };
-  if (!masked) issue(qt0, 0);
 
-  bf16x8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    kf[ks] = *reinterpret_cast<const bf16x8 *>(qp + HD + (int64_t)kv * ld + ks * 16 + g * 8);
-    vf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 2 * HD + (int64_t)kv * ld + ks * 16 + g * 8);
-  }
-  f32x16 dk[MT], dv[MT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
-
-  auto step = [&](int qt, auto stage_c) {
-    constexpr int ST = decltype(stage_c)::value;
-    DL_WAIT_VM0;
-    __builtin_amdgcn_s_barrier();
-    if (qt + 1 < n_q) issue(qt + 1, ST ^ 1);
-    if (qt * 64 + 63 < k0) return;  // every query of the tile precedes this wave's keys
-    const char *Qt = smem + ST * STAGE_B, *Gt = Qt + TILE_B;
-    const float *Ls = reinterpret_cast<const float *>(smem + 2 * STAGE_B + ST * 512), *Ds = Ls + 64;
-    const bool diag = qt * 64 < k0 + 31;
-    // LDS latency is far longer than one matrix instruction, so every fragment is requested well before its use:
-    // the 16 row fragments of a 32-query half-tile before the score products, the 16 transposed fragments while
-    // the softmax arithmetic runs, and the next half-tile's row fragments under the dK/dV products.
-    bf16x8 qf[KS], gf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) { qf[ks] = frag(Qt, ro.fo[ks]); gf[ks] = frag(Gt, ro.fo[ks]); }
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-      __builtin_amdgcn_sched_barrier(0);
+  for (int item = 0; item < 2; ++item) {
+    const int kb = item ? nkb - 1 - pr : pr;
+    if (item && 2 * pr == nkb - 1) break;  // an odd number of key blocks: the middle one has no partner
+    const int k0 = kb * 128 + wk * 32, kv = k0 + c;
+    const int qt0 = kb * 2;                          // first query tile at or below the diagonal
+    const int n_steps = masked ? 0 : N / 64 - qt0;   // query tiles qt0 .. N/64 - 1
+    const int n_ph = 2 * n_steps;                    // phases of 32 queries; the consumer runs one phase behind
+    if (n_steps) issue(qt0, 0);
+    // phase ph covers queries [q_lo, q_lo + 32) of tile ph / 2 (stage (ph / 2) % 3); it is skipped when all of them
+    // precede this wave's keys
+    auto q_lo_of = [&](int ph) { return (qt0 + (ph >> 1)) * 64 + (ph & 1) * 32; };
+    if (producer) {
+      bf16x8 kf[KS], vf[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        s = MFMA(qf[ks], kf[ks], s);
-        dp = MFMA(gf[ks], vf[ks], dp);
+        kf[ks] = *reinterpret_cast<const bf16x8 *>(qp + HD + (int64_t)kv * ld + ks * 16 + g * 8);
+        vf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 2 * HD + (int64_t)kv * ld + ks * 16 + g * 8);
       }
-      bf16x8 tg[2][MT], tq[2][MT];
-      auto load_tr = [&](int t) {
+      DL_WAIT_VM0;  // the first tile, and the key / value fragments
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
-          tg[t][i] = frag_tr(Gt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]);
-          tq[t][i] = frag_tr(Qt + (mt * 32 + 16 * t) * 256, ro.ta[i], ro.tb[i]);
+      for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));  // (used here: the compiler may not sink the loads, and its waits for them, into the loop)
+      __builtin_amdgcn_s_barrier();
+      for (int ph = 0; ph <= n_ph; ++ph) {
+        const int t = ph >> 1, mt = ph & 1;
+        if (mt == 0 && t + 1 < n_steps) issue(qt0 + t + 1, (t + 1) % 3);
+        const int q_lo = q_lo_of(ph);
+        if (ph < n_ph && q_lo + 31 >= k0) {
+          const int st = t % 3;
+          const char *Qt = smem + st * STAGE_B + mt * 8192, *Gt = Qt + TILE_B;
+          const float *Ls = reinterpret_cast<const float *>(smem + DKV_LD_OFF + st * 512) + mt * 32, *Ds = Ls + 64;
+          f32x16 sv, dp;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { sv[r] = 0.f; dp[r] = 0.f; }
+          // all 16 fragments are requested before the first product (the producer has the registers for it): one LDS
+          // round trip per phase instead of one per pair of products
+          bf16x8 qf[KS], gf[KS];
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) { qf[ks] = frag(Qt, ro.fo[ks]); gf[ks] = frag(Gt, ro.fo[ks]); }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            sv = MFMA(qf[ks], kf[ks], sv);
+            dp = MFMA(gf[ks], vf[ks], dp);
+          }
+          const bool diag = q_lo < k0 + 31;  // some query of the phase precedes some key of the wave
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const int qrow = 8 * r4 + 4 * g;  // first of 4 consecutive query rows inside the phase
+            const f32x4 L4 = *reinterpret_cast<const f32x4 *>(Ls + qrow), D4 = *reinterpret_cast<const f32x4 *>(Ds + qrow);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int r = 4 * r4 + e;
+              float x = fmaf(sv[r], sc, -L4[e] * kLog2e);
+              if (diag && q_lo + qrow + e < kv) x = -INFINITY;
+              const float pv = fast_exp2(x);
+              dp[r] = pv * fmaf(dp[r], scale, -D4[e] * scale);  // dS
+              sv[r] = pv;
+            }
+          }
+          u32x4 *X = reinterpret_cast<u32x4 *>(smem + DKV_XCH_OFF + ((ph & 1) * 4 + wk) * 4096);
+          X[lane] = __builtin_bit_cast(u32x4, pack8(sv, 0));
+          X[64 + lane] = __builtin_bit_cast(u32x4, pack8(sv, 8));
+          X[128 + lane] = __builtin_bit_cast(u32x4, pack8(dp, 0));
+          X[192 + lane] = __builtin_bit_cast(u32x4, pack8(dp, 8));
         }
-      };
-      load_tr(0);
-      __builtin_amdgcn_sched_barrier(0);
+        if (mt) DL_WAIT_VM0;  // end of a tile: this wave's pieces of the next one have landed
+        DL_WAIT_LGKM0;        // the hand-over is written
+        __builtin_amdgcn_s_barrier();
+      }
+    } else {
+      f32x16 dk[MT], dv[MT];
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int qrow = mt * 32 + 8 * r4 + 4 * g;  // first of 4 consecutive query rows inside the tile
-        const f32x4 L4 = *reinterpret_cast<const f32x4 *>(Ls + qrow), D4 = *reinterpret_cast<const f32x4 *>(Ds + qrow);
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * r4 + e;
-          float x = fmaf(s[r], sc, -L4[e] * kLog2e);
-          if (diag && qt * 64 + qrow + e < kv) x = -INFINITY;  // (the compiler keeps two copies of the loop body)
-          const float p = fast_exp2(x);
-          dp[r] = p * fmaf(dp[r], scale, -D4[e] * scale);  // dS
-          s[r] = p;
+        for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+      DL_WAIT_VM0;
+      __builtin_amdgcn_s_barrier();
+      for (int ph = 0; ph <= n_ph; ++ph) {
+        const int t = ph >> 1, mt = ph & 1;
+        if (mt == 0 && t + 1 < n_steps) issue(qt0 + t + 1, (t + 1) % 3);
+        const int pp = ph - 1;  // the phase the producer finished before the last barrier
+        if (pp >= 0 && q_lo_of(pp) + 31 >= k0) {
+          const int st = (pp >> 1) % 3, mp = pp & 1;
+          const char *Qt = smem + st * STAGE_B + mp * 8192, *Gt = Qt + TILE_B;
+          const u32x4 *X = reinterpret_cast<const u32x4 *>(smem + DKV_XCH_OFF + ((pp & 1) * 4 + wk) * 4096);
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2) {
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, X[t2 * 64 + lane]), df = __builtin_bit_cast(bf16x8, X[128 + t2 * 64 + lane]);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+              dv[i] = MFMA(frag_tr(Gt + 16 * t2 * 256, ro.ta[i], ro.tb[i]), pf, dv[i]);
+              dk[i] = MFMA(frag_tr(Qt + 16 * t2 * 256, ro.ta[i], ro.tb[i]), df, dk[i]);
+            }
+          }
         }
+        if (mt) DL_WAIT_VM0;
+        DL_WAIT_LGKM0;  // every LDS read of the phase has returned before the stage and the hand-over area are released
+        __builtin_amdgcn_s_barrier();
       }
-      const bf16x8 pf0 = pack8(s, 0), df0 = pack8(dp, 0), pf1 = pack8(s, 8), df1 = pack8(dp, 8);
-      __builtin_amdgcn_sched_barrier(0);
-      load_tr(1);
-      __builtin_amdgcn_sched_barrier(0);
+      if (rope) rope_grad(dk, rope, kv, g);
+      uint16_t *op = dqkv + ((int64_t)b * N + kv) * ld + (int64_t)h * DH;
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        dv[i] = MFMA(tg[0][i], pf0, dv[i]);
-        dk[i] = MFMA(tq[0][i], df0, dk[i]);
-      }
-      if (mt == 0) {
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) { qf[ks] = frag(Qt + 8192, ro.fo[ks]); gf[ks] = frag(Gt + 8192, ro.fo[ks]); }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        dv[i] = MFMA(tg[1][i], pf1, dv[i]);
-        dk[i] = MFMA(tq[1][i], df1, dk[i]);
-      }
+        for (int j = 0; j < 4; ++j) {
+          u32x2 wkk = {pack2(dk[i][4 * j], dk[i][4 * j + 1]), pack2(dk[i][4 * j + 2], dk[i][4 * j + 3])};
+          u32x2 wv = {pack2(dv[i][4 * j], dv[i][4 * j + 1]), pack2(dv[i][4 * j + 2], dv[i][4 * j + 3])};
+          *reinterpret_cast<u32x2 *>(op + HD + i * 32 + 8 * j + 4 * g) = wkk;
+          *reinterpret_cast<u32x2 *>(op + 2 * HD + i * 32 + 8 * j + 4 * g) = wv;
+        }
     }
-  };
-  for (int qt = qt0; qt < n_q; qt += 2) {  // qt0 and n_q are even
-    step(qt, std::integral_constant<int, 0>());
-    step(qt + 1, std::integral_constant<int, 1>());
+    __builtin_amdgcn_s_barrier();  // the next item's first loads overwrite stage 0
   }
-  if (rope) rope_grad(dk, rope, kv, g);
-  uint16_t *op = dqkv + ((int64_t)b * N + kv) * ld + (int64_t)h * DH;
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      u32x2 wk = {pack2(dk[i][4 * j], dk[i][4 * j + 1]), pack2(dk[i][4 * j + 2], dk[i][4 * j + 3])};
-      u32x2 wv = {pack2(dv[i][4 * j], dv[i][4 * j + 1]), pack2(dv[i][4 * j + 2], dv[i][4 * j + 3])};
-      *reinterpret_cast<u32x2 *>(op + HD + i * 32 + 8 * j + 4 * g) = wk;
-      *reinterpret_cast<u32x2 *>(op + 2 * HD + i * 32 + 8 * j + 4 * g) = wv;
-    }
 }
 
 }  // namespace dl
@@ -905,7 +936,8 @@ twist_status twist_attention_bwd_mfma(twist_ctx *ctx, const void *qkv, const flo
   if (dh == 128 && dl_ok(ctx, N, Hs, dh)) {
     const float *rt = rope_tab && (reinterpret_cast<uintptr_t>(rope_tab) % 16) == 0 ? rope_tab : nullptr;
     hipLaunchKernelGGL(dl::flash_bwd_dq_dl_kernel, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, rt, keep);
-    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, grid, block, 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, rt, keep);
+    hipLaunchKernelGGL(dl::flash_bwd_dkv_dl_kernel, dim3((unsigned)((int64_t)((N / 128 + 1) / 2) * B * Hs)), dim3(512), 0, ctx->stream, x, gout, lse, delta, dx, N, Hs, scale, rt,
+                       keep);
     *rope_done = rt != nullptr;
   } else if (dh == 128) {
     hipLaunchKernelGGL(flash_bwd_dq_kernel<128>, grid, block, 0, ctx->stream, x, gout, o32, lse, delta, dx, N, Hs, scale, keep);
