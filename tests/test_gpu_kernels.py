@@ -154,7 +154,9 @@ def test_embedding_forward_and_backward(lib, dtype, positions):
 
 
 @pytest.mark.parametrize("dtype,dh,N,choice", [(BF, 128, 256, {}), (BF, 128, 128, {"staged_attention": True}), (BF, 64, 128, {}),
-                                               (BF, 32, 40, {}), (BF, 128, 128, {"plain_only": True}), (F32, 16, 37, {})])
+                                               (BF, 32, 40, {}), (BF, 128, 128, {"plain_only": True}), (F32, 16, 37, {}),
+                                               # one, three and five key blocks: the dK/dV kernel pairs key blocks, the middle one stays single
+                                               (BF, 128, 128, {}), (BF, 128, 384, {}), (BF, 128, 640, {})])
 def test_attention_head_mask(lib, dtype, dh, N, choice):
     """Masked TwIST's head mask inside the attention kernels (Section 4.1): a masked head's output and its q, k, v gradients
     are exact zeros, the kept heads' results are bit-identical to the unmasked call, in every kernel family (direct-to-LDS,
@@ -184,7 +186,7 @@ def test_attention_head_mask(lib, dtype, dh, N, choice):
         assert rel_fro(d[:, i].reshape(B, N, Hs, dh), want) <= _tol(dtype), (i, rel_fro(d[:, i].reshape(B, N, Hs, dh), want))
 
 
-@pytest.mark.parametrize("dh,N,choice", [(128, 256, {}), (128, 128, {"staged_attention": True}), (64, 128, {}), (32, 40, {})])
+@pytest.mark.parametrize("dh,N,choice", [(128, 256, {}), (128, 384, {}), (128, 128, {"staged_attention": True}), (64, 128, {}), (32, 40, {})])
 def test_attention_backward_through_rotary_positions(lib, dh, N, choice):
     """The q and k gradients turned back through the rotary embedding (inside the direct-to-LDS kernels, by a separate
     rotation behind the others): the checker's attention backward followed by the inverse rotation."""
