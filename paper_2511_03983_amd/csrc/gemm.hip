@@ -17,6 +17,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+// two floats to a packed pair of bf16, round to nearest even, in one instruction (v_cvt_pk_bf16_f32): the same bits as f2bf for
+// every finite value and infinity (the software form costs about eight instructions and a branch per value, which showed in
+// the epilogue: 40.6 -> 39.9 ms per forward+backward pass)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ uint16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
   if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
@@ -462,12 +471,29 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
       if (ncol + e < N) bias[e] = bf2f(static_cast<const uint16_t *>(ep.bias)[ncol + e]);
   }
   const bool vec = ep.vec_ok && ncol + 3 < N;
+  // a tile that lies inside the output and needs nothing but the conversion (most projections): no edge tests, no arithmetic
+  const bool bare = ep.vec_ok && !ep.bias && !ep.residual && ep.alpha == 1.f && m0 + 256 <= M && n0 + 256 <= N;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * EPI_LD + 32 * j + c] = acc[i][j][r];
+    if (bare) {
+      const int64_t o0 = (int64_t)(m0 + wm + 32 * i + g) * ep.ldc + ncol;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const f32x4 v4 = *reinterpret_cast<const f32x4 *>(stage + (2 * p + g) * EPI_LD + 4 * c);
+        const int64_t o = o0 + 2 * p * ep.ldc;
+        if (ep.out_f32) {
+          __builtin_nontemporal_store(v4, reinterpret_cast<f32x4 *>(static_cast<float *>(outp) + o));
+        } else {
+          const u32x2 w = {pack_bf16(v4[0], v4[1]), pack_bf16(v4[2], v4[3])};
+          __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outp) + o));
+        }
+      }
+      continue;
+    }
 #pragma unroll 4
     for (int p = 0; p < 16; ++p) {
       const int row = 2 * p + g, ml = wm + 32 * i + row;
@@ -487,7 +513,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(int M, int N, int K, const
           const f32x4 w = {v[0], v[1], v[2], v[3]};
           __builtin_nontemporal_store(w, reinterpret_cast<f32x4 *>(static_cast<float *>(outp) + o));
         } else {
-          const u32x2 w = {(uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16)};
+          const u32x2 w = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
           __builtin_nontemporal_store(w, reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(outp) + o));
         }
       } else {
