@@ -253,30 +253,61 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(int M, int N, in
     __syncthreads();
   }
 
-  // Epilogue.  Accumulator layout of a 32x32 tile: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4.
-  const int esz = ep.out_f32 ? 4 : 2;
+  // Epilogue.  A 32x32 accumulator tile holds column lane % 32 and rows 8*(r/4) + 4*(lane/32) + r%4, which would store
+  // 2-byte pieces; each wave instead turns its results through LDS (the operand stages are free now), 32 rows at a time,
+  // so that a lane owns 4 consecutive columns and a store instruction writes four rows of 64 columns.
+  static_assert(TN == 2 && sizeof(As) >= WM * WN * 32 * 72 * 4, "staging of 32 x 64 results per wave fits the A stages");
+  constexpr int LDE = 72;  // floats per staged row: rows 4 apart (the two half-waves of a write) are 32 banks apart
+  float *stage = reinterpret_cast<float *>(&As[0][0]) + wave * (32 * LDE);
+  const int c = lane & 31, g = lane >> 5, c16 = lane & 15, rs = lane >> 4;
   const int rows_left = M - m0;
-  char *cbase = static_cast<char *>(ep.out) + ((int64_t)m0 * ep.ldc) * esz;
-  const __amdgpu_buffer_rsrc_t crs = make_rsrc(cbase, (uint32_t)(((int64_t)(min(rows_left, BM) - 1) * ep.ldc + N) * esz));
-  const float *rbase = ep.residual ? ep.residual + (int64_t)m0 * ep.ldc : nullptr;
-  const __amdgpu_buffer_rsrc_t rrs = make_rsrc(rbase, rbase ? (uint32_t)(((int64_t)(min(rows_left, BM) - 1) * ep.ldc + N) * 4) : 0u);
+  const int ncol = n0 + wn + 4 * c16;  // first of this lane's 4 columns
+  float bias[4] = {0.f, 0.f, 0.f, 0.f};
+  if (ep.bias) {
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn + j * 32 + (lane & 31);
-    const bool n_ok = n < N;
-    float bias = 0.f;
-    if (ep.bias && n_ok) bias = bf2f(static_cast<const uint16_t *>(ep.bias)[n]);
+    for (int e = 0; e < 4; ++e)
+      if (ncol + e < N) bias[e] = bf2f(static_cast<const uint16_t *>(ep.bias)[ncol + e]);
+  }
+  const bool vec = ep.vec_ok && ncol + 3 < N;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int ml = wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const uint32_t eoff = (n_ok && ml < rows_left) ? (uint32_t)(ml * ep.ldc + n) : kOob;
-        float v = (acc[i][j][r] + bias) * ep.alpha;
-        if (ep.residual) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rrs, eoff == kOob ? kOob : eoff * 4, 0, 0));
-        if (ep.out_f32) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), crs, eoff == kOob ? kOob : eoff * 4, 0, 0);
-        else __builtin_amdgcn_raw_buffer_store_b16(f2bf(v), crs, eoff == kOob ? kOob : eoff * 2, 0, 0);
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * g + (r & 3)) * LDE + 32 * j + c] = acc[i][j][r];
+#pragma unroll 4
+    for (int p = 0; p < 8; ++p) {
+      const int row = 4 * p + rs, ml = wm + 32 * i + row;
+      const f32x4 v4 = *reinterpret_cast<const f32x4 *>(stage + row * LDE + 4 * c16);
+      if (ml >= rows_left || ncol >= N) continue;
+      const int64_t o = (int64_t)(m0 + ml) * ep.ldc + ncol;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (v4[e] + bias[e]) * ep.alpha;
+      if (vec) {
+        if (ep.residual) {
+          const f32x4 rr = *reinterpret_cast<const f32x4 *>(ep.residual + o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += rr[e];
+        }
+        if (ep.out_f32) {
+          const f32x4 w = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4 *>(static_cast<float *>(ep.out) + o) = w;
+        } else {
+          const u32x2 w = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(ep.out) + o) = w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ncol + e >= N) break;
+          float x = v[e];
+          if (ep.residual) x += ep.residual[o + e];
+          if (ep.out_f32) static_cast<float *>(ep.out)[o + e] = x;
+          else static_cast<uint16_t *>(ep.out)[o + e] = f2bf(x);
+        }
       }
+    }
   }
 }
 
